@@ -1,0 +1,248 @@
+"""Circuit layer of the oracle: BNN layers as Boolean circuits.  TEST INFRASTRUCTURE ONLY.
+
+Follows the TAPAS paper: a layer is z = sign(Wx + b) with sign(0) = +1
+(Sec. 3.2 'Technical details'); on bits it is XNOR with the weight, popcount S,
+then the test 2S >= d - b (steps 1-4 there).  With the weights in the clear the
+XNOR is a copy or a negation of the encrypted input (Sec. 4.1.1), a zero weight
+drops the input (Sec. 4.3), the popcount is a reduce tree of half adders and
+ripple-carry adders (Sec. 4.1.1 'Reduce tree adder'), and the comparison with the
+plaintext threshold is the LSB-to-MSB chain of Algorithm 1 with its multiplexers
+specialised by the known threshold bit: MUX(s, 1, o) = OR(s, o) and
+MUX(s, o, 0) = AND(s, o).
+
+Everything here is plain Python on small integers; gate records use the same
+16-byte layout as the C oracle's batch entry point.
+"""
+import numpy as np
+
+from .oracle import GATE_DTYPE, OP
+
+CONST0 = "const0"
+CONST1 = "const1"
+
+
+class Circuit:
+    """A wire pool and a gate list.  Wires 0..n_inputs-1 are the encrypted inputs,
+    wire n_inputs is a noiseless encryption of 0, wire n_inputs+1 of 1, every gate
+    appends one wire.  A literal is (wire, neg)."""
+
+    def __init__(self, n_inputs):
+        self.n_inputs = n_inputs
+        self.c0 = n_inputs
+        self.c1 = n_inputs + 1
+        self.n_wires = n_inputs + 2
+        self.gates = []
+
+    def gate(self, op, a, b):
+        out = self.n_wires
+        self.n_wires += 1
+        self.gates.append((OP[op], a[1], b[1], 0, a[0], b[0], out))
+        return (out, 0)
+
+    def gate_array(self):
+        return np.array(self.gates, dtype=GATE_DTYPE)
+
+
+def bitlen(x):
+    return int(x).bit_length()
+
+
+def add_numbers(cir, a, b):
+    """Ripple-carry sum of two little-endian encrypted numbers (bits, max).
+    Bit 0 is a half adder (XOR, AND); a full-adder cell is XOR, XOR, AND, AND, OR;
+    beyond the shorter operand the cell is a half adder on the carry.  A carry is
+    only computed where the plaintext maxima allow one."""
+    (abits, amax), (bbits, bmax) = a, b
+    if len(bbits) > len(abits):
+        abits, bbits = bbits, abits
+    wa, wb = len(abits), len(bbits)
+    M = amax + bmax
+    wout = bitlen(M)
+    out = [cir.gate("XOR", abits[0], bbits[0])]
+    c = cir.gate("AND", abits[0], bbits[0]) if wout > 1 else None
+    for i in range(1, wa):
+        need_carry = i + 1 < wout
+        if i < wb:
+            t = cir.gate("XOR", abits[i], bbits[i])
+            out.append(cir.gate("XOR", t, c))
+            if need_carry:
+                g = cir.gate("AND", abits[i], bbits[i])
+                p = cir.gate("AND", t, c)
+                c = cir.gate("OR", g, p)
+        else:
+            out.append(cir.gate("XOR", abits[i], c))
+            if need_carry:
+                c = cir.gate("AND", abits[i], c)
+    if wout > wa:
+        out.append(c)
+    assert len(out) == wout
+    return (out, M)
+
+
+def popcount_tree(cir, leaves):
+    """Reduce tree: add neighbours pairwise, an odd last element moves on unchanged."""
+    L = [([lit], 1) for lit in leaves]
+    if not L:
+        return ([], 0)
+    while len(L) > 1:
+        nxt = [add_numbers(cir, L[i], L[i + 1]) for i in range(0, len(L) - 1, 2)]
+        if len(L) & 1:
+            nxt.append(L[-1])
+        L = nxt
+    return L[0]
+
+
+def threshold_chain(cir, number, T):
+    """[S >= T] for the encrypted number S (Algorithm 1, started at 'equal so far
+    counts as true' so that the result is >= as the paper's step 4 requires)."""
+    bits, m = number
+    if T <= 0:
+        return CONST1
+    if T > m:
+        return CONST0
+    o = CONST1
+    for i, s in enumerate(bits):
+        Ti = (T >> i) & 1
+        if o is CONST1:
+            if Ti:
+                o = s
+        elif Ti:
+            o = cir.gate("AND", s, o)
+        else:
+            o = cir.gate("OR", s, o)
+    return o
+
+
+def neuron(cir, x_literals, w_row, T, out_bits=0):
+    """One output unit.  x_literals[i] is the literal of input i; w in {-1,0,+1}.
+    Returns one literal/constant (T given) or out_bits popcount literals (T None)."""
+    leaves = []
+    for lit, w in zip(x_literals, w_row):
+        if w > 0:
+            leaves.append(lit)
+        elif w < 0:
+            leaves.append((lit[0], lit[1] ^ 1))
+    S = popcount_tree(cir, leaves)
+    if T is not None:
+        return [threshold_chain(cir, S, int(T))]
+    bits = list(S[0]) + [CONST0] * max(0, out_bits - len(S[0]))
+    assert len(bits) == out_bits, "out_bits too small for this popcount"
+    return bits
+
+
+def dense_layer(d, W, T, out_bits=0):
+    """Circuit of a fully connected layer.  Returns (circuit, outputs)."""
+    cir = Circuit(d)
+    x = [(i, 0) for i in range(d)]
+    outs = []
+    for j in range(W.shape[0]):
+        outs += neuron(cir, x, W[j], None if T is None else T[j], out_bits)
+    return cir, outs
+
+
+def conv_pixel_literals(cir, C_, H, Wd, kh, kw, stride, pad, y, x):
+    """Receptive field of output pixel (y, x): (c, ky, kx) row-major; a pixel
+    outside the image is the noiseless encryption of 0."""
+    lits = []
+    for c in range(C_):
+        for ky in range(kh):
+            for kx in range(kw):
+                iy, ix = y * stride + ky - pad, x * stride + kx - pad
+                if 0 <= iy < H and 0 <= ix < Wd:
+                    lits.append(((c * H + iy) * Wd + ix, 0))
+                else:
+                    lits.append((cir.c0, 0))
+    return lits
+
+
+def conv_layer(C_, H, Wd, K, T, stride, pad, pixels=None):
+    """Circuit of a convolution layer (or of the listed output pixels (o, y, x) only)."""
+    O, _, kh, kw = K.shape
+    Ho = (H + 2 * pad - kh) // stride + 1
+    Wo = (Wd + 2 * pad - kw) // stride + 1
+    cir = Circuit(C_ * H * Wd)
+    if pixels is None:
+        pixels = [(o, y, x) for o in range(O) for y in range(Ho) for x in range(Wo)]
+    outs = []
+    for (o, y, x) in pixels:
+        lits = conv_pixel_literals(cir, C_, H, Wd, kh, kw, stride, pad, y, x)
+        outs += neuron(cir, lits, K[o].reshape(-1), T[o])
+    return cir, outs
+
+
+# ---------------------------------------------------------------------------
+# plaintext evaluation
+# ---------------------------------------------------------------------------
+_TRUTH = {OP["NAND"]: lambda a, b: 1 - (a & b), OP["AND"]: lambda a, b: a & b,
+          OP["OR"]: lambda a, b: a | b, OP["NOR"]: lambda a, b: 1 - (a | b),
+          OP["XOR"]: lambda a, b: a ^ b, OP["XNOR"]: lambda a, b: 1 - (a ^ b)}
+
+
+def eval_plain(cir, in_bits, outs):
+    """Evaluate the circuit on plaintext bits; returns the output bits."""
+    w = np.zeros(cir.n_wires, np.uint8)
+    w[:cir.n_inputs] = in_bits
+    w[cir.c0], w[cir.c1] = 0, 1
+    for (op, n0, n1, _, i0, i1, o) in cir.gates:
+        w[o] = _TRUTH[op](int(w[i0]) ^ n0, int(w[i1]) ^ n1)
+    res = []
+    for lit in outs:
+        if lit is CONST0:
+            res.append(0)
+        elif lit is CONST1:
+            res.append(1)
+        else:
+            res.append(int(w[lit[0]]) ^ lit[1])
+    return np.array(res, np.uint8)
+
+
+def eval_encrypted(keys, cir, in_cts, outs, threads=1):
+    """Evaluate the circuit on ciphertexts with the oracle gate; returns (out cts, wires)."""
+    n1 = keys.P.n + 1
+    wires = np.zeros((cir.n_wires, n1), np.uint32)
+    wires[:cir.n_inputs] = in_cts
+    wires[cir.c0] = keys.trivial(0)
+    wires[cir.c1] = keys.trivial(1)
+    if cir.gates:
+        keys.run_gates(cir.gate_array(), wires, threads)
+    res = np.zeros((len(outs), n1), np.uint32)
+    for k, lit in enumerate(outs):
+        if lit is CONST0:
+            res[k] = keys.trivial(0)
+        elif lit is CONST1:
+            res[k] = keys.trivial(1)
+        else:
+            res[k] = wires[lit[0]] if not lit[1] else (0 - wires[lit[0]]).astype(np.uint32)
+    return res, wires
+
+
+# ---------------------------------------------------------------------------
+# plaintext BNN layers on integers (Sec. 3.2: z = sign(Wx + b), via popcounts)
+# ---------------------------------------------------------------------------
+def dense_plain(x_bits, W, T):
+    """Bits out: [popcount(XNOR(w, x) over w != 0) >= T]; popcounts if T is None."""
+    xs = 2 * x_bits.astype(np.int64) - 1                 # {0,1} -> {-1,+1}
+    agree = (W.astype(np.int64) * xs[None, :]) > 0       # XNOR on the +-1 encoding
+    S = agree.sum(axis=1)
+    if T is None:
+        return S
+    return (S >= np.asarray(T)).astype(np.uint8)
+
+
+def conv_plain(x_bits, K, T, stride, pad):
+    """x_bits [C,H,W] in {0,1}; padding pixels are bit 0 (i.e. -1), XNORed like any other."""
+    C_, H, Wd = x_bits.shape
+    O, _, kh, kw = K.shape
+    Ho = (H + 2 * pad - kh) // stride + 1
+    Wo = (Wd + 2 * pad - kw) // stride + 1
+    xp = np.zeros((C_, H + 2 * pad, Wd + 2 * pad), np.int64)
+    xp[:, pad:pad + H, pad:pad + Wd] = x_bits
+    xs = 2 * xp - 1
+    out = np.zeros((O, Ho, Wo), np.uint8)
+    for o in range(O):
+        for y in range(Ho):
+            for x in range(Wo):
+                patch = xs[:, y * stride:y * stride + kh, x * stride:x * stride + kw]
+                S = int(((K[o].astype(np.int64) * patch) > 0).sum())
+                out[o, y, x] = S >= T[o]
+    return out

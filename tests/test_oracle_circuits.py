@@ -1,0 +1,214 @@
+"""Pins for the oracle's circuit layer: reduce-tree popcount, comparator chain,
+dense / convolution lowering, against integer popcounts, the paper's closed form for
+a BNN unit, the gate counts the paper states, and a library correlation."""
+import itertools
+import os
+
+import numpy as np
+import pytest
+from scipy.signal import correlate
+
+import workloads
+from oracle import circuits as cc
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def paper_counts():
+    d = {}
+    for line in open(os.path.join(GOLD, "paper_gate_counts.txt")):
+        if line.strip() and not line.startswith("#"):
+            k, v = line.split()
+            d[k] = int(v)
+    return d
+
+
+def popcount_bits(m, weights=None):
+    cir = cc.Circuit(m)
+    w = np.ones(m, np.int8) if weights is None else weights
+    outs = cc.neuron(cir, [(i, 0) for i in range(m)], w, None, out_bits=max(1, int(m).bit_length()))
+    return cir, outs
+
+
+# --------------------------------------------------------------------------- popcount tree
+@pytest.mark.parametrize("m", range(1, 13))
+def test_popcount_tree_exhaustive(m):
+    cir, outs = popcount_bits(m)
+    for bits in itertools.product((0, 1), repeat=m):
+        got = cc.eval_plain(cir, np.array(bits, np.uint8), outs)
+        assert sum(int(b) << i for i, b in enumerate(got)) == sum(bits)
+
+
+@pytest.mark.parametrize("m", [13, 31, 64, 90, 144, 257, 784, 1704])
+def test_popcount_tree_random_with_signed_weights(m):
+    rng = np.random.default_rng(m)
+    w = rng.choice(np.array([-1, 0, 1], np.int8), m, p=[0.4, 0.2, 0.4])
+    cir, outs = popcount_bits(m, w)
+    for trial in range(6):
+        x = (rng.random(m) < (0.5, 0.05, 0.95)[trial % 3]).astype(np.uint8)
+        got = cc.eval_plain(cir, x, outs)
+        want = int(((x == 1) & (w == 1)).sum() + ((x == 0) & (w == -1)).sum())
+        assert sum(int(b) << i for i, b in enumerate(got)) == want
+    for x in (np.zeros(m, np.uint8), np.ones(m, np.uint8)):
+        got = cc.eval_plain(cir, x, outs)
+        want = int(((x == 1) & (w == 1)).sum() + ((x == 0) & (w == -1)).sum())
+        assert sum(int(b) << i for i, b in enumerate(got)) == want
+
+
+def test_adder_gate_counts_match_paper_statement():
+    """A half adder is 2 gates; a full-adder cell is 5 gates (the paper's '5k gates per k-bit
+    RC adder'); this build's k-bit adder starts with a half adder at bit 0, hence 5k - 3."""
+    pc = paper_counts()
+    cir = cc.Circuit(2)
+    cc.add_numbers(cir, ([(0, 0)], 1), ([(1, 0)], 1))
+    assert len(cir.gates) == pc["half_adder_gates"]
+    for k in range(2, 9):
+        cir = cc.Circuit(2 * k)
+        a = ([(i, 0) for i in range(k)], 2**k - 1)
+        b = ([(k + i, 0) for i in range(k)], 2**k - 1)
+        cc.add_numbers(cir, a, b)
+        assert len(cir.gates) == pc["rc_adder_gates_per_bit"] * k - 3
+
+
+@pytest.mark.parametrize("k", range(1, 11))
+def test_tree_gate_count_closed_form_power_of_two(k):
+    d = 2**k
+    cir, _ = popcount_bits(d)
+    want = d + sum((d >> j) * (5 * j - 3) for j in range(2, k + 1))
+    assert len(cir.gates) == want
+
+
+def depth_of(cir):
+    depth = np.zeros(cir.n_wires, np.int64)
+    for (_, _, _, _, i0, i1, o) in cir.gates:
+        depth[o] = 1 + max(depth[i0], depth[i1])
+    return int(depth.max())
+
+
+def test_benchmark_neuron_sizes():
+    """Tree sizes / depths of the benchmark's unit circuits; the comparator adds 1..w-1 gates
+    and one to w-1 levels (w = bit width of the popcount)."""
+    for m, tree, tree_depth, thresholds in ((144, 966, 25, range(55, 90)), (256, 1745, 28, range(96, 161)),
+                                            (784, 5434, 35, range(300, 485))):
+        cir, _ = popcount_bits(m)
+        assert len(cir.gates) == tree and depth_of(cir) == tree_depth
+        w = int(m).bit_length()
+        for t in thresholds:
+            cir = cc.Circuit(m)
+            cc.neuron(cir, [(i, 0) for i in range(m)], np.ones(m, np.int8), t)
+            assert tree + 1 <= len(cir.gates) <= tree + w - 1
+            assert depth_of(cir) == tree_depth + 1          # the chain runs beside the ripple carry
+
+
+# --------------------------------------------------------------------------- comparator
+@pytest.mark.parametrize("m", [1, 2, 3, 5, 8, 13, 31, 32, 33, 64])
+def test_threshold_chain_all_S_all_T(m):
+    for T in range(-1, m + 3):
+        cir = cc.Circuit(m)
+        outs = cc.neuron(cir, [(i, 0) for i in range(m)], np.ones(m, np.int8), T)
+        for S in range(m + 1):
+            x = np.zeros(m, np.uint8)
+            x[:S] = 1
+            assert cc.eval_plain(cir, x, outs)[0] == (1 if S >= T else 0), (m, T, S)
+
+
+def test_threshold_chain_gate_budget():
+    """At most w-1 two-input gates for a w-bit popcount (Algorithm 1 would use w MUX gates)."""
+    for m in (7, 144, 256, 784):
+        w = int(m).bit_length()
+        base = len(popcount_bits(m)[0].gates)
+        for T in range(1, m + 1):
+            cir = cc.Circuit(m)
+            cc.neuron(cir, [(i, 0) for i in range(m)], np.ones(m, np.int8), T)
+            assert len(cir.gates) - base <= w - 1
+
+
+# --------------------------------------------------------------------------- layers
+def test_threshold_form_equals_paper_sign_form():
+    """[S >= ceil((d-b)/2)] equals sign(2 S - d + b) with sign(0) = +1 (Sec. 3.2, step 4)."""
+    rng = np.random.default_rng(0)
+    for _ in range(300):
+        d = int(rng.integers(1, 200))
+        b = int(rng.integers(-d - 3, d + 4))
+        w = 2 * rng.integers(0, 2, d) - 1
+        x = rng.integers(0, 2, d).astype(np.uint8)
+        z = 1 if int((w * (2 * x.astype(int) - 1)).sum()) + b >= 0 else 0
+        T = -((b - d) // 2)                       # ceil((d - b) / 2)
+        assert cc.dense_plain(x, w.reshape(1, d).astype(np.int8), np.array([T]))[0] == z
+
+
+@pytest.mark.parametrize("d,p,sparse", [(9, 5, False), (90, 3, False), (64, 6, True), (200, 4, True)])
+def test_dense_circuit_equals_integer_layer(d, p, sparse):
+    rng = np.random.default_rng(d * p)
+    W = (2 * rng.integers(0, 2, (p, d)) - 1).astype(np.int8)
+    if sparse:
+        W[rng.random((p, d)) < 0.5] = 0
+    m = (W != 0).sum(axis=1)
+    T = np.array([rng.integers(-1, mm + 2) for mm in m], np.int32)
+    cir, outs = cc.dense_layer(d, W, T)
+    cirS, outsS = cc.dense_layer(d, W, None, out_bits=10)
+    for _ in range(8):
+        x = rng.integers(0, 2, d).astype(np.uint8)
+        assert np.array_equal(cc.eval_plain(cir, x, outs), cc.dense_plain(x, W, T))
+        bits = cc.eval_plain(cirS, x, outsS).reshape(p, 10)
+        assert np.array_equal((bits.astype(np.int64) << np.arange(10)).sum(axis=1), cc.dense_plain(x, W, None))
+
+
+def test_conv_plain_against_library_correlation():
+    c4 = workloads.cfg4(C=3, H=7, Wd=6, O=4)
+    x, K, T = c4["x"], c4["K"], c4["T"]
+    xs = np.pad(2 * x.astype(np.int64) - 1, ((0, 0), (1, 1), (1, 1)), constant_values=-1)
+    for o in range(K.shape[0]):
+        dot = correlate(xs, K[o].astype(np.int64), mode="valid")[0]       # sum_c,ky,kx K * x
+        S = (dot + K[o].size) // 2                                         # agreements
+        for Tt in (T[o], 10, 14, 20):
+            want = (S >= Tt).astype(np.uint8)
+            got = cc.conv_plain(x, K, np.full(K.shape[0], Tt), 1, 1)[o]
+            assert np.array_equal(got, want)
+
+
+def test_conv_circuit_equals_integer_layer():
+    rng = np.random.default_rng(3)
+    C_, H, Wd, O = 2, 5, 4, 3
+    x = rng.integers(0, 2, (C_, H, Wd)).astype(np.uint8)
+    K = (2 * rng.integers(0, 2, (O, C_, 3, 3)) - 1).astype(np.int8)
+    T = rng.integers(6, 13, O).astype(np.int32)
+    cir, outs = cc.conv_layer(C_, H, Wd, K, T, 1, 1)
+    got = cc.eval_plain(cir, x.reshape(-1), outs).reshape(O, H, Wd)
+    assert np.array_equal(got, cc.conv_plain(x, K, T, 1, 1))
+    # every pixel sums all 18 taps: padding is an (encrypted) zero, not a dropped input
+    n_per_pixel = len(cir.gates) / (O * H * Wd)
+    one = cc.Circuit(18)
+    cc.neuron(one, [(i, 0) for i in range(18)], np.ones(18, np.int8), 9)
+    assert abs(n_per_pixel - len(one.gates)) <= 4
+    # stride 2, no padding
+    cir, outs = cc.conv_layer(C_, H, Wd, K, T, 2, 0)
+    got = cc.eval_plain(cir, x.reshape(-1), outs).reshape(O, 2, 1)
+    assert np.array_equal(got, cc.conv_plain(x, K, T, 2, 0))
+
+
+# --------------------------------------------------------------------------- encrypted
+def test_small_dense_layer_encrypted_toy(orc, toy_keys):
+    rng = np.random.default_rng(11)
+    d, p = 9, 4
+    W = rng.choice(np.array([-1, 0, 1], np.int8), (p, d))
+    T = np.array([0, 3, 2, 20], np.int32)
+    x = rng.integers(0, 2, d).astype(np.uint8)
+    cir, outs = cc.dense_layer(d, W, T)
+    ct = toy_keys.encrypt(x, 3)
+    res, wires = cc.eval_encrypted(toy_keys, cir, ct, outs, threads=4)
+    assert np.array_equal(toy_keys.decrypt(res), cc.dense_plain(x, W, T))
+    res1, _ = cc.eval_encrypted(toy_keys, cir, ct, outs, threads=1)
+    assert np.array_equal(res, res1)
+
+
+def test_one_neuron_encrypted_real_parameters(orc, real_keys):
+    rng = np.random.default_rng(12)
+    d = 12
+    W = (2 * rng.integers(0, 2, (1, d)) - 1).astype(np.int8)
+    x = rng.integers(0, 2, d).astype(np.uint8)
+    ct = real_keys.encrypt(x, 77)
+    for T in (5, 7):
+        cir, outs = cc.dense_layer(d, W, np.array([T]))
+        res, _ = cc.eval_encrypted(real_keys, cir, ct, outs, threads=8)
+        assert real_keys.decrypt(res)[0] == cc.dense_plain(x, W, np.array([T]))[0]
