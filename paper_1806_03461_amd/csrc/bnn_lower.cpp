@@ -1,0 +1,289 @@
+// Lowering of binary-neural-network layers to gate circuits, and the layer entry points.
+//
+// A unit computes z = sign(w.x + b) (TAPAS, Sec. 3.2): XNOR each input with its weight bit,
+// count the ones (S), test 2S >= d - b.  With plaintext weights the XNOR is a copy or a
+// negation of the input ciphertext (Sec. 4.1.1) and costs nothing: it becomes the sign flag of
+// the first gate that consumes the input.  Zero weights drop the input (Sec. 4.3).  The count
+// is the reduce tree of half adders and ripple-carry adders of Sec. 4.1.1; the comparison with
+// the plaintext threshold is the least-to-most-significant chain of Algorithm 1, each
+// multiplexer specialised by its known threshold bit (MUX(s,1,o) = OR, MUX(s,o,0) = AND) and
+// started from "equal so far counts as true" so that the result is S >= T.
+#include <algorithm>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+
+#include "common.h"
+#include "kernels.h"
+
+namespace tfhe {
+int run_gate_stream(tfhe_cloud_key *ck, const tfhe_gate_rec *gates, size_t ngates, uint32_t *wires,
+                    size_t nwires, hipStream_t stream);
+int ensure_uploaded(tfhe_cloud_key *ck);
+}
+
+namespace {
+
+using tfhe::set_error;
+
+// A signal: a wire with an optional negation, or a known constant.
+struct Sig {
+    int32_t wire;   // -1: constant
+    int32_t flag;   // wire: negated?  constant: its value
+    static Sig of(int32_t w, bool neg = false) { return Sig{w, neg ? 1 : 0}; }
+    static Sig constant(int v) { return Sig{-1, v}; }
+    bool is_const() const { return wire < 0; }
+};
+
+// A little-endian unsigned number of signals with a known upper bound.
+struct Number {
+    std::vector<Sig> bits;
+    int64_t bound = 0;
+};
+
+class Builder {
+public:
+    explicit Builder(int32_t n_inputs) : next_(n_inputs + 2), zero_(n_inputs), one_(n_inputs + 1) {}
+    int32_t zero_wire() const { return zero_; }
+    int32_t wires() const { return next_; }
+    std::vector<tfhe_gate_rec> &gates() { return gates_; }
+
+    Sig emit(int op, Sig a, Sig b) {
+        tfhe_gate_rec r{};
+        r.op = (uint8_t)op; r.neg0 = (uint8_t)a.flag; r.neg1 = (uint8_t)b.flag;
+        r.in0 = a.wire; r.in1 = b.wire; r.out = next_++;
+        gates_.push_back(r);
+        return Sig::of(r.out);
+    }
+
+    static int width_of(int64_t bound) { int w = 0; while (bound >> w) ++w; return w; }
+
+    // Ripple-carry addition; carries are produced only where the bounds allow one.
+    Number add(const Number &p, const Number &q) {
+        const Number &longer = q.bits.size() > p.bits.size() ? q : p;
+        const Number &shorter = q.bits.size() > p.bits.size() ? p : q;
+        Number sum;
+        sum.bound = p.bound + q.bound;
+        const int width = width_of(sum.bound);
+        const int nl = (int)longer.bits.size(), ns = (int)shorter.bits.size();
+        Sig carry = Sig::constant(0);
+        bool have_carry = false;
+        for (int pos = 0; pos < nl; ++pos) {
+            const bool wants_carry = pos + 1 < width;
+            const Sig x = longer.bits[pos];
+            if (pos == 0) {                                   // half adder
+                const Sig y = shorter.bits[0];
+                sum.bits.push_back(emit(TFHE_XOR, x, y));
+                if (wants_carry) { carry = emit(TFHE_AND, x, y); have_carry = true; }
+            } else if (pos < ns) {                            // full adder
+                const Sig y = shorter.bits[pos];
+                const Sig t = emit(TFHE_XOR, x, y);
+                sum.bits.push_back(emit(TFHE_XOR, t, carry));
+                if (wants_carry) {
+                    const Sig gen = emit(TFHE_AND, x, y);
+                    const Sig prop = emit(TFHE_AND, t, carry);
+                    carry = emit(TFHE_OR, gen, prop);
+                }
+            } else {                                          // half adder on the carry
+                sum.bits.push_back(emit(TFHE_XOR, x, carry));
+                if (wants_carry) carry = emit(TFHE_AND, x, carry);
+            }
+        }
+        if (width > nl && have_carry) sum.bits.push_back(carry);
+        return sum;
+    }
+
+    Number popcount(const std::vector<Sig> &leaves) {
+        std::vector<Number> level;
+        level.reserve(leaves.size());
+        for (const Sig &s : leaves) { Number one; one.bits.push_back(s); one.bound = 1; level.push_back(std::move(one)); }
+        if (level.empty()) return Number{};
+        while (level.size() > 1) {
+            std::vector<Number> next;
+            next.reserve(level.size() / 2 + 1);
+            size_t i = 0;
+            for (; i + 1 < level.size(); i += 2) next.push_back(add(level[i], level[i + 1]));
+            if (i < level.size()) next.push_back(std::move(level[i]));
+            level.swap(next);
+        }
+        return std::move(level[0]);
+    }
+
+    // [S >= T]
+    Sig at_least(const Number &S, int64_t T) {
+        if (T <= 0) return Sig::constant(1);
+        if (T > S.bound) return Sig::constant(0);
+        bool undecided_true = true;          // nothing but "equal so far" seen: result is the constant 1
+        Sig o = Sig::constant(1);
+        for (size_t pos = 0; pos < S.bits.size(); ++pos) {
+            const bool tbit = (T >> pos) & 1;
+            if (undecided_true) {
+                if (tbit) { o = S.bits[pos]; undecided_true = false; }
+            } else {
+                o = emit(tbit ? TFHE_AND : TFHE_OR, S.bits[pos], o);
+            }
+        }
+        return o;
+    }
+
+    // one output unit over the listed inputs
+    void unit(const std::vector<Sig> &inputs, const int8_t *w, const int32_t *T, int out_bits,
+              std::vector<tfhe_out_ref> &outs) {
+        std::vector<Sig> leaves;
+        leaves.reserve(inputs.size());
+        for (size_t i = 0; i < inputs.size(); ++i) {
+            if (w[i] == 0) continue;
+            Sig s = inputs[i];
+            if (w[i] < 0) s.flag ^= 1;
+            leaves.push_back(s);
+        }
+        const Number S = popcount(leaves);
+        if (T) {
+            const Sig o = at_least(S, *T);
+            outs.push_back(tfhe_out_ref{o.wire, o.flag});
+        } else {
+            for (int bpos = 0; bpos < out_bits; ++bpos) {
+                if (bpos < (int)S.bits.size()) outs.push_back(tfhe_out_ref{S.bits[bpos].wire, S.bits[bpos].flag});
+                else outs.push_back(tfhe_out_ref{-1, 0});
+            }
+        }
+    }
+
+private:
+    std::vector<tfhe_gate_rec> gates_;
+    int32_t next_, zero_, one_;
+};
+
+template <class T>
+int hand_over(const std::vector<T> &v, T **out, size_t *count) {
+    *count = v.size();
+    *out = (T *)malloc(std::max<size_t>(1, v.size()) * sizeof(T));
+    if (!*out) return set_error(TFHE_E_ALLOC, "out of memory");
+    if (!v.empty()) memcpy(*out, v.data(), v.size() * sizeof(T));
+    return TFHE_OK;
+}
+
+int check_weights(const int8_t *W, size_t count) {
+    for (size_t i = 0; i < count; ++i)
+        if (W[i] < -1 || W[i] > 1) return set_error(TFHE_E_PARAM, "weight %zu is %d, not in {-1,0,1}", i, W[i]);
+    return TFHE_OK;
+}
+
+int lower_dense(int d, const int8_t *W, const int32_t *T, int p, int out_bits, Builder &b,
+                std::vector<tfhe_out_ref> &outs) {
+    if (d < 1 || p < 1) return set_error(TFHE_E_SIZE, "layer sizes must be positive");
+    if (!W) return set_error(TFHE_E_NULL, "W is NULL");
+    if (!T) {
+        if (out_bits < 1 || out_bits > 31) return set_error(TFHE_E_SIZE, "out_bits must be in [1,31]");
+        int64_t most = 0;
+        for (int j = 0; j < p; ++j) {
+            int64_t m = 0;
+            for (int i = 0; i < d; ++i) m += W[(size_t)j * d + i] != 0;
+            most = std::max(most, m);
+        }
+        if (Builder::width_of(most) > out_bits)
+            return set_error(TFHE_E_SIZE, "out_bits=%d cannot hold a popcount of %lld", out_bits, (long long)most);
+    }
+    if (int rc = check_weights(W, (size_t)d * p)) return rc;
+    std::vector<Sig> x(d);
+    for (int i = 0; i < d; ++i) x[i] = Sig::of(i);
+    for (int j = 0; j < p; ++j) b.unit(x, W + (size_t)j * d, T ? T + j : nullptr, out_bits, outs);
+    return TFHE_OK;
+}
+
+int lower_conv(int C, int H, int Wd, const int8_t *K, int O, int kh, int kw, int stride, int pad,
+               const int32_t *T, Builder &b, std::vector<tfhe_out_ref> &outs) {
+    if (C < 1 || H < 1 || Wd < 1 || O < 1 || kh < 1 || kw < 1 || stride < 1 || pad < 0)
+        return set_error(TFHE_E_SIZE, "bad convolution shape");
+    if (!K || !T) return set_error(TFHE_E_NULL, "K or T is NULL");
+    if (H + 2 * pad < kh || Wd + 2 * pad < kw) return set_error(TFHE_E_SIZE, "kernel larger than padded image");
+    const size_t taps = (size_t)C * kh * kw;
+    if (int rc = check_weights(K, taps * O)) return rc;
+    const int Ho = (H + 2 * pad - kh) / stride + 1, Wo = (Wd + 2 * pad - kw) / stride + 1;
+    std::vector<Sig> field(taps);
+    for (int o = 0; o < O; ++o)
+        for (int y = 0; y < Ho; ++y)
+            for (int x = 0; x < Wo; ++x) {
+                size_t t = 0;
+                for (int c = 0; c < C; ++c)
+                    for (int ky = 0; ky < kh; ++ky)
+                        for (int kx = 0; kx < kw; ++kx, ++t) {
+                            const int iy = y * stride + ky - pad, ix = x * stride + kx - pad;
+                            const bool inside = iy >= 0 && iy < H && ix >= 0 && ix < Wd;
+                            field[t] = Sig::of(inside ? (c * H + iy) * Wd + ix : b.zero_wire());
+                        }
+                b.unit(field, K + (size_t)o * taps, T + o, 0, outs);
+            }
+    return TFHE_OK;
+}
+
+// wires = [inputs | noiseless 0 | noiseless 1 | gate outputs]; run; gather the outputs
+int evaluate(tfhe_cloud_key *ck, Builder &b, const std::vector<tfhe_out_ref> &outs, const uint32_t *x,
+             int n_inputs, uint32_t *out, hipStream_t stream) {
+    const int words = ck->params.n + 1;
+    const size_t nwires = (size_t)b.wires();
+    if (int rc = ck->ws_wires.reserve(nwires * words * sizeof(uint32_t))) return rc;
+    if (int rc = ck->ws_outs.reserve(std::max<size_t>(1, outs.size()) * sizeof(tfhe_out_ref))) return rc;
+    uint32_t *wires = (uint32_t *)ck->ws_wires.ptr;
+    TFHE_HIP(hipMemcpyAsync(wires, x, (size_t)n_inputs * words * sizeof(uint32_t), hipMemcpyDeviceToDevice, stream));
+    if (int rc = tfhe::launch_fill_trivial(wires + (size_t)n_inputs * words, words, 0, stream)) return rc;
+    if (int rc = tfhe::launch_fill_trivial(wires + (size_t)(n_inputs + 1) * words, words, 1, stream)) return rc;
+    if (int rc = tfhe::run_gate_stream(ck, b.gates().data(), b.gates().size(), wires, nwires, stream)) return rc;
+    TFHE_HIP(hipMemcpyAsync(ck->ws_outs.ptr, outs.data(), outs.size() * sizeof(tfhe_out_ref),
+                            hipMemcpyHostToDevice, stream));
+    TFHE_HIP(hipStreamSynchronize(stream));   // `outs` is a host temporary of the caller
+    return tfhe::launch_gather_outputs(wires, (const tfhe_out_ref *)ck->ws_outs.ptr, out, outs.size(), words, stream);
+}
+
+}  // namespace
+
+extern "C" {
+
+int bnn_dense_lower(int d, const int8_t *W, const int32_t *T, int p, int out_bits, tfhe_gate_rec **gates,
+                    size_t *ngates, tfhe_out_ref **outs, size_t *nouts, size_t *nwires) {
+    if (!gates || !ngates || !outs || !nouts || !nwires) return set_error(TFHE_E_NULL, "NULL output pointer");
+    Builder b(d);
+    std::vector<tfhe_out_ref> o;
+    if (int rc = lower_dense(d, W, T, p, out_bits, b, o)) return rc;
+    if (int rc = hand_over(b.gates(), gates, ngates)) return rc;
+    if (int rc = hand_over(o, outs, nouts)) { free(*gates); return rc; }
+    *nwires = (size_t)b.wires();
+    return TFHE_OK;
+}
+
+int bnn_conv_lower(int C, int H, int Wd, const int8_t *K, int O, int kh, int kw, int stride, int pad,
+                   const int32_t *T, tfhe_gate_rec **gates, size_t *ngates, tfhe_out_ref **outs, size_t *nouts,
+                   size_t *nwires) {
+    if (!gates || !ngates || !outs || !nouts || !nwires) return set_error(TFHE_E_NULL, "NULL output pointer");
+    if (C < 1 || H < 1 || Wd < 1) return set_error(TFHE_E_SIZE, "bad convolution shape");
+    Builder b(C * H * Wd);
+    std::vector<tfhe_out_ref> o;
+    if (int rc = lower_conv(C, H, Wd, K, O, kh, kw, stride, pad, T, b, o)) return rc;
+    if (int rc = hand_over(b.gates(), gates, ngates)) return rc;
+    if (int rc = hand_over(o, outs, nouts)) { free(*gates); return rc; }
+    *nwires = (size_t)b.wires();
+    return TFHE_OK;
+}
+
+int bnn_dense_encrypted(tfhe_cloud_key *ck, const uint32_t *x, int d, const int8_t *W, const int32_t *T, int p,
+                        uint32_t *out, int out_bits, void *stream) {
+    if (int rc = tfhe::ensure_uploaded(ck)) return rc;
+    if (!x || !out) return set_error(TFHE_E_NULL, "NULL ciphertext buffer");
+    Builder b(d);
+    std::vector<tfhe_out_ref> o;
+    if (int rc = lower_dense(d, W, T, p, out_bits, b, o)) return rc;
+    return evaluate(ck, b, o, x, d, out, (hipStream_t)stream);
+}
+
+int bnn_conv_encrypted(tfhe_cloud_key *ck, const uint32_t *x, int C, int H, int Wd, const int8_t *K, int O,
+                       int kh, int kw, int stride, int pad, const int32_t *T, uint32_t *out, void *stream) {
+    if (int rc = tfhe::ensure_uploaded(ck)) return rc;
+    if (!x || !out) return set_error(TFHE_E_NULL, "NULL ciphertext buffer");
+    if (C < 1 || H < 1 || Wd < 1) return set_error(TFHE_E_SIZE, "bad convolution shape");
+    Builder b(C * H * Wd);
+    std::vector<tfhe_out_ref> o;
+    if (int rc = lower_conv(C, H, Wd, K, O, kh, kw, stride, pad, T, b, o)) return rc;
+    return evaluate(ck, b, o, x, C * H * Wd, out, (hipStream_t)stream);
+}
+
+}  // extern "C"

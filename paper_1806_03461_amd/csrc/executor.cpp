@@ -1,0 +1,299 @@
+// Server-side host code: cloud-key upload, batched gate calls, the gate-stream executor.
+//
+// The data-parallel structure is the one the TAPAS paper points out (Sec. 4): gates at the
+// same depth of a circuit are independent, and so are the output units of a layer (Sec. 5.3).
+// The executor sorts a circuit by depth and runs each depth as large batches of the two
+// kernels (blind rotation, then key switch) on the caller's stream, without host
+// synchronisation in between.
+#include <algorithm>
+#include <cmath>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+
+#include "common.h"
+#include "kernels.h"
+
+namespace tfhe {
+
+int DeviceBuffer::reserve(size_t want) {
+    if (want <= bytes) return TFHE_OK;
+    if (ptr) { TFHE_HIP(hipFree(ptr)); ptr = nullptr; bytes = 0; }
+    // grow geometrically so that a sequence of slightly larger calls does not reallocate each time
+    size_t grown = std::max(want, bytes + bytes / 2);
+    hipError_t e = hipMalloc(&ptr, grown);
+    if (e != hipSuccess && grown != want) { grown = want; e = hipMalloc(&ptr, grown); }
+    if (e != hipSuccess) {
+        ptr = nullptr;
+        return set_error(TFHE_E_ALLOC, "hipMalloc of %zu bytes failed: %s", grown, hipGetErrorString(e));
+    }
+    bytes = grown;
+    return TFHE_OK;
+}
+
+void DeviceBuffer::release() {
+    if (ptr) (void)hipFree(ptr);
+    ptr = nullptr;
+    bytes = 0;
+}
+
+namespace {
+
+constexpr size_t kChunkGates = 32768;   // gates per kernel pair; bounds the extract workspace (134 MB)
+
+int gates_per_group() {
+    static int cached = 0;
+    if (!cached) {
+        const char *e = getenv("TFHE_GATES_PER_GROUP");
+        int v = e ? atoi(e) : 0;
+        cached = (v >= 1 && v <= 3) ? v : 1;
+    }
+    return cached;
+}
+
+int check_cloud_key(const tfhe_cloud_key *ck) {
+    if (!ck) return set_error(TFHE_E_NULL, "cloud key is NULL");
+    if (ck->magic != TFHE_CK_MAGIC) return set_error(TFHE_E_PARAM, "not a cloud key");
+    return check_params_gpu(&ck->params);
+}
+
+int begin_timed(tfhe_cloud_key *ck, int kind, hipStream_t stream, TimedLaunch &tl) {
+    tl.kind = kind;
+    TFHE_HIP(hipEventCreate(&tl.start));
+    TFHE_HIP(hipEventCreate(&tl.stop));
+    TFHE_HIP(hipEventRecord(tl.start, stream));
+    (void)ck;
+    return TFHE_OK;
+}
+
+int end_timed(tfhe_cloud_key *ck, hipStream_t stream, TimedLaunch &tl) {
+    TFHE_HIP(hipEventRecord(tl.stop, stream));
+    ck->timed.push_back(tl);
+    return TFHE_OK;
+}
+
+// One batch of `count` gates: blind rotation into the extract workspace, then key switch.
+int run_batch(tfhe_cloud_key *ck, const tfhe_gate_rec *d_recs, int uniform_op, const uint32_t *in0,
+              const uint32_t *in1, uint32_t *out, size_t count, hipStream_t stream) {
+    const tfhe_params &P = ck->params;
+    BlindRotateArgs br{};
+    br.recs = d_recs; br.uniform_op = uniform_op; br.in0 = in0; br.in1 = in1;
+    br.ext = (uint32_t *)ck->ws_ext.ptr; br.count = count;
+    br.bk_fft = ck->d_bk_fft; br.tables = ck->d_tables; br.n = P.n; br.bgbit = P.bk_Bgbit;
+    br.margin = ck->margin ? ck->d_margin : nullptr;
+    KeySwitchArgs ks{};
+    ks.ext = br.ext; ks.recs = d_recs; ks.out = out; ks.count = count; ks.ksk = ck->d_ksk;
+    ks.n = P.n; ks.t = P.ks_t; ks.basebit = P.ks_basebit;
+
+    TimedLaunch tl{};
+    if (ck->profile) if (int rc = begin_timed(ck, 0, stream, tl)) return rc;
+    if (int rc = launch_blind_rotate(br, gates_per_group(), stream)) return rc;
+    if (ck->profile) if (int rc = end_timed(ck, stream, tl)) return rc;
+    if (ck->profile) if (int rc = begin_timed(ck, 1, stream, tl)) return rc;
+    if (int rc = launch_key_switch(ks, stream)) return rc;
+    if (ck->profile) if (int rc = end_timed(ck, stream, tl)) return rc;
+    if (ck->profile) ck->prof_gates += count;
+    return TFHE_OK;
+}
+
+}  // namespace
+
+// Evaluate host gate records (validated, any order within the topological constraint) on device wires.
+int run_gate_stream(tfhe_cloud_key *ck, const tfhe_gate_rec *gates, size_t ngates, uint32_t *wires,
+                    size_t nwires, hipStream_t stream) {
+    if (ngates == 0) return TFHE_OK;
+    if (ngates > (size_t)INT32_MAX || nwires > (size_t)INT32_MAX)
+        return set_error(TFHE_E_SIZE, "too many gates or wires");
+    // writer of each wire; an input must be produced by an earlier record or by nobody
+    std::vector<int32_t> writer(nwires, -1);
+    for (size_t g = 0; g < ngates; ++g) {
+        const tfhe_gate_rec &r = gates[g];
+        if (r.op > TFHE_XNOR || r.neg0 > 1 || r.neg1 > 1)
+            return set_error(TFHE_E_PARAM, "gate %zu: bad opcode or flag", g);
+        if (r.in0 < 0 || r.in1 < 0 || r.out < 0 || (size_t)r.in0 >= nwires || (size_t)r.in1 >= nwires ||
+            (size_t)r.out >= nwires)
+            return set_error(TFHE_E_SIZE, "gate %zu: wire index out of range", g);
+        if (writer[r.out] >= 0) return set_error(TFHE_E_PARAM, "gate %zu: wire %d written twice", g, r.out);
+        writer[r.out] = (int32_t)g;
+    }
+    std::vector<int32_t> level(ngates);
+    std::vector<int32_t> depth(nwires, 0);
+    int32_t max_level = 0;
+    for (size_t g = 0; g < ngates; ++g) {
+        const tfhe_gate_rec &r = gates[g];
+        if (writer[r.in0] >= (int32_t)g || writer[r.in1] >= (int32_t)g)
+            return set_error(TFHE_E_PARAM, "gate %zu reads a wire written by itself or a later record", g);
+        const int32_t lv = 1 + std::max(depth[r.in0], depth[r.in1]);
+        level[g] = lv;
+        depth[r.out] = lv;
+        max_level = std::max(max_level, lv);
+    }
+    // counting sort by depth
+    std::vector<size_t> start(max_level + 2, 0);
+    for (size_t g = 0; g < ngates; ++g) ++start[level[g] + 1];
+    for (int32_t l = 1; l <= max_level + 1; ++l) start[l] += start[l - 1];
+    std::vector<tfhe_gate_rec> sorted(ngates);
+    {
+        std::vector<size_t> at(start.begin(), start.end());
+        for (size_t g = 0; g < ngates; ++g) sorted[at[level[g]]++] = gates[g];
+    }
+    if (int rc = ck->ws_gates.reserve(ngates * sizeof(tfhe_gate_rec))) return rc;
+    const size_t biggest = std::min(kChunkGates, ngates);
+    if (int rc = ck->ws_ext.reserve(biggest * (size_t)(ck->params.N + 1) * sizeof(uint32_t))) return rc;
+    // synchronous with respect to the host buffer, ordered on the stream
+    TFHE_HIP(hipMemcpyAsync(ck->ws_gates.ptr, sorted.data(), ngates * sizeof(tfhe_gate_rec),
+                            hipMemcpyHostToDevice, stream));
+    TFHE_HIP(hipStreamSynchronize(stream));
+    const tfhe_gate_rec *d_recs = (const tfhe_gate_rec *)ck->ws_gates.ptr;
+    for (int32_t l = 1; l <= max_level; ++l) {
+        for (size_t at = start[l]; at < start[l + 1]; at += kChunkGates) {
+            const size_t cnt = std::min(kChunkGates, start[l + 1] - at);
+            if (int rc = run_batch(ck, d_recs + at, 0, wires, wires, wires, cnt, stream)) return rc;
+        }
+    }
+    return TFHE_OK;
+}
+
+int ensure_uploaded(tfhe_cloud_key *ck) {
+    if (int rc = check_cloud_key(ck)) return rc;
+    if (ck->uploaded) return TFHE_OK;
+    return tfhe_cloud_key_upload(ck);
+}
+
+}  // namespace tfhe
+
+using namespace tfhe;
+
+extern "C" {
+
+int tfhe_cloud_key_upload(tfhe_cloud_key *ck) {
+    if (int rc = check_cloud_key(ck)) return rc;
+    if (ck->uploaded) return TFHE_OK;
+    const tfhe_params &P = ck->params;
+    int count = 0;
+    TFHE_HIP(hipGetDeviceCount(&count));
+    if (count < 1) return set_error(TFHE_E_HIP, "no HIP device");
+    TFHE_HIP(hipGetDevice(&ck->device));
+
+    // twiddle tables: w512^k and psi^j, evaluated in extended precision
+    std::vector<double2> tables(1024);
+    const long double pi = 3.14159265358979323846264338327950288L;
+    for (int k = 0; k < 512; ++k) {
+        tables[k] = make_double2((double)cosl(2 * pi * k / 512), (double)sinl(2 * pi * k / 512));
+        tables[512 + k] = make_double2((double)cosl(pi * k / 1024), (double)sinl(pi * k / 1024));
+    }
+    TFHE_HIP(hipMalloc((void **)&ck->d_tables, tables.size() * sizeof(double2)));
+    TFHE_HIP(hipMemcpy(ck->d_tables, tables.data(), tables.size() * sizeof(double2), hipMemcpyHostToDevice));
+
+    // key-switching key plus one zero row (what digit 0 reads)
+    const size_t ksk_words = ck->ksk_raw.size(), row = (size_t)P.n + 1;
+    TFHE_HIP(hipMalloc((void **)&ck->d_ksk, (ksk_words + row) * sizeof(uint32_t)));
+    TFHE_HIP(hipMemcpy(ck->d_ksk, ck->ksk_raw.data(), ksk_words * sizeof(uint32_t), hipMemcpyHostToDevice));
+    TFHE_HIP(hipMemset(ck->d_ksk + ksk_words, 0, row * sizeof(uint32_t)));
+
+    // bootstrapping key: raw to device, transform on device, raw copy released
+    uint32_t *d_raw = nullptr;
+    const size_t bk_bytes = ck->bk_raw.size() * sizeof(uint32_t);
+    TFHE_HIP(hipMalloc((void **)&d_raw, bk_bytes));
+    TFHE_HIP(hipMemcpy(d_raw, ck->bk_raw.data(), bk_bytes, hipMemcpyHostToDevice));
+    const size_t fft_words = (size_t)P.n * 16 * 512;
+    TFHE_HIP(hipMalloc((void **)&ck->d_bk_fft, fft_words * sizeof(double2)));
+    if (int rc = launch_bk_to_spectrum(d_raw, ck->d_bk_fft, ck->d_tables, P.n, nullptr)) return rc;
+    TFHE_HIP(hipDeviceSynchronize());
+    TFHE_HIP(hipFree(d_raw));
+
+    TFHE_HIP(hipMalloc((void **)&ck->d_margin, sizeof(double)));
+    TFHE_HIP(hipMemset(ck->d_margin, 0, sizeof(double)));
+    ck->uploaded = true;
+    return TFHE_OK;
+}
+
+void tfhe_free_cloud_key(tfhe_cloud_key *ck) {
+    if (!ck || ck->magic != TFHE_CK_MAGIC) return;
+    if (ck->uploaded) {
+        (void)hipDeviceSynchronize();
+        (void)hipFree(ck->d_ksk);
+        (void)hipFree(ck->d_bk_fft);
+        (void)hipFree(ck->d_tables);
+        (void)hipFree(ck->d_margin);
+    }
+    for (auto &tl : ck->timed) { (void)hipEventDestroy(tl.start); (void)hipEventDestroy(tl.stop); }
+    ck->ws_gates.release(); ck->ws_ext.release(); ck->ws_wires.release(); ck->ws_outs.release();
+    ck->magic = 0;
+    delete ck;
+}
+
+int tfhe_gate_batch(tfhe_cloud_key *ck, int op, const uint32_t *a, const uint32_t *b, uint32_t *out,
+                    size_t count, void *stream) {
+    if (int rc = ensure_uploaded(ck)) return rc;
+    if (op < TFHE_NAND || op > TFHE_XNOR) return set_error(TFHE_E_PARAM, "unknown gate opcode %d", op);
+    if (count == 0) return TFHE_OK;
+    if (!a || !b || !out) return set_error(TFHE_E_NULL, "NULL ciphertext buffer");
+    const size_t words = (size_t)ck->params.n + 1;
+    const size_t biggest = std::min(kChunkGates, count);
+    if (int rc = ck->ws_ext.reserve(biggest * (size_t)(ck->params.N + 1) * sizeof(uint32_t))) return rc;
+    for (size_t at = 0; at < count; at += kChunkGates) {
+        const size_t cnt = std::min(kChunkGates, count - at);
+        if (int rc = run_batch(ck, nullptr, op, a + at * words, b + at * words, out + at * words, cnt,
+                               (hipStream_t)stream))
+            return rc;
+    }
+    return TFHE_OK;
+}
+
+int tfhe_gate_stream(tfhe_cloud_key *ck, const tfhe_gate_rec *gates, size_t ngates, uint32_t *wires,
+                     size_t nwires, void *stream) {
+    if (int rc = ensure_uploaded(ck)) return rc;
+    if (ngates == 0) return TFHE_OK;
+    if (!gates || !wires) return set_error(TFHE_E_NULL, "NULL gates or wires");
+    return run_gate_stream(ck, gates, ngates, wires, nwires, (hipStream_t)stream);
+}
+
+int tfhe_profile_enable(tfhe_cloud_key *ck, int on) {
+    if (int rc = check_cloud_key(ck)) return rc;
+    ck->profile = on != 0;
+    return TFHE_OK;
+}
+
+int tfhe_profile_read(tfhe_cloud_key *ck, tfhe_profile *out, int reset) {
+    if (int rc = check_cloud_key(ck)) return rc;
+    if (!out) return set_error(TFHE_E_NULL, "NULL profile output");
+    for (auto &tl : ck->timed) {
+        TFHE_HIP(hipEventSynchronize(tl.stop));
+        float ms = 0;
+        TFHE_HIP(hipEventElapsedTime(&ms, tl.start, tl.stop));
+        ck->prof_ms[tl.kind] += ms;
+        ck->prof_launches[tl.kind] += 1;
+        (void)hipEventDestroy(tl.start);
+        (void)hipEventDestroy(tl.stop);
+    }
+    ck->timed.clear();
+    out->blind_rotate_ms = ck->prof_ms[0];
+    out->key_switch_ms = ck->prof_ms[1];
+    out->blind_rotate_launches = ck->prof_launches[0];
+    out->key_switch_launches = ck->prof_launches[1];
+    out->gates = ck->prof_gates;
+    if (reset) {
+        ck->prof_ms[0] = ck->prof_ms[1] = 0;
+        ck->prof_launches[0] = ck->prof_launches[1] = 0;
+        ck->prof_gates = 0;
+    }
+    return TFHE_OK;
+}
+
+int tfhe_rounding_margin_enable(tfhe_cloud_key *ck, int on) {
+    if (int rc = ensure_uploaded(ck)) return rc;
+    ck->margin = on != 0;
+    if (on) TFHE_HIP(hipMemset(ck->d_margin, 0, sizeof(double)));
+    return TFHE_OK;
+}
+
+int tfhe_rounding_margin_read(tfhe_cloud_key *ck, double *max_fraction) {
+    if (int rc = ensure_uploaded(ck)) return rc;
+    if (!max_fraction) return set_error(TFHE_E_NULL, "NULL output");
+    TFHE_HIP(hipDeviceSynchronize());
+    TFHE_HIP(hipMemcpy(max_fraction, ck->d_margin, sizeof(double), hipMemcpyDeviceToHost));
+    return TFHE_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,37 @@
+// Launchers of the gfx950 kernels (kernels.hip), called by the host executor.
+#pragma once
+#include "common.h"
+
+namespace tfhe {
+
+struct BlindRotateArgs {
+    const tfhe_gate_rec *recs;   // device; NULL: gate i reads in0[i], in1[i] with uniform_op
+    int uniform_op;
+    const uint32_t *in0, *in1;   // device wire arrays the records index into
+    uint32_t *ext;               // device [count][1025]: extracted samples
+    size_t count;
+    const double2 *bk_fft;       // device [n][4][4][512]
+    const double2 *tables;       // device [1024]
+    int n, bgbit;
+    double *margin;              // device, optional: largest rounding distance seen
+};
+
+struct KeySwitchArgs {
+    const uint32_t *ext;         // device [count][1025]
+    const tfhe_gate_rec *recs;   // device; NULL: gate i writes out[i]
+    uint32_t *out;               // device wire array
+    size_t count;
+    const uint32_t *ksk;         // device [1024][t][2^basebit - 1][n+1] plus one zero row
+    int n, t, basebit;
+};
+
+size_t blind_rotate_lds_bytes(int gates_per_group);
+int launch_bk_to_spectrum(const uint32_t *bk_raw, double2 *bk_fft, const double2 *tables, int n,
+                          hipStream_t stream);
+int launch_blind_rotate(const BlindRotateArgs &a, int gates_per_group, hipStream_t stream);
+int launch_key_switch(const KeySwitchArgs &a, hipStream_t stream);
+int launch_gather_outputs(const uint32_t *wires, const tfhe_out_ref *refs, uint32_t *out, size_t count,
+                          int words, hipStream_t stream);
+int launch_fill_trivial(uint32_t *ct, int words, int bit, hipStream_t stream);
+
+}  // namespace tfhe

@@ -1,0 +1,419 @@
+// gfx950 kernels: transform-domain bootstrapping key, blind rotation, key switch, output gather.
+//
+// The bootstrapped gate is the CGGI gate the TAPAS paper builds its circuits from
+// (Sec. 3.1.2, Sec. 4.1); the paper gives no construction, the steps are the public ones.
+//
+// Exactness.  Each blind-rotation step needs, for both TRLWE components c,
+//     sum_{r<4} digit_r(X) * BK_i[r][c](X)   mod (X^1024 + 1, 2^32),
+// digit_r with coefficients in [-512, 512).  Every 32-bit key coefficient is split into two
+// signed 16-bit limbs, key = lo + 2^16 hi (mod 2^32); the two integer products
+// sum_r digit_r * lo_r and sum_r digit_r * hi_r have coefficients below 2^36 in magnitude and
+// are computed with double-precision FFTs whose rounding error stays orders of magnitude below
+// 1/2, so rounding the inverse transform to the nearest integer gives them exactly; the result
+// is lo-sum + 2^16 * hi-sum (mod 2^32).  MI355X issues FP64 FMAs at full vector rate, which
+// makes this cheaper than any 32-bit-integer number-theoretic transform on its VALU.
+#include <hip/hip_runtime.h>
+
+#include "common.h"
+#include "fft512.h"
+#include "kernels.h"
+
+namespace tfhe {
+
+using namespace fft512;
+
+namespace {
+
+constexpr int kN = 1024;
+constexpr int kHalf = 512;
+constexpr int kThreadsPerGate = 256;
+constexpr uint32_t kEighth = 1u << 29;
+
+__device__ __forceinline__ void wave_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// Forward transform of the 8 folded, twisted points held in x; leaves the spectrum in buf in
+// slot order (slot = 64 * register + lane).
+__device__ __forceinline__ void forward_to_slots(double2 (&x)[8], const Lane &ln, double2 *buf, int L) {
+    fwd_pass1_store(x, ln, buf, L);
+    wave_sync();
+    fwd_pass2_load(x, buf, L);
+    wave_sync();
+    fwd_pass2_store(x, ln, buf, L);
+    wave_sync();
+    fwd_pass3(x, buf, L);
+    wave_sync();
+#pragma unroll
+    for (int k = 0; k < 8; ++k) buf[k * 64 + L] = x[k];
+}
+
+// Inverse transform of the spectrum held in buf (slot order); x[m] is 512 times the folded,
+// still twisted point L + 64 m.
+__device__ __forceinline__ void inverse_from_slots(double2 (&x)[8], const Lane &ln, double2 *buf, int L) {
+#pragma unroll
+    for (int k = 0; k < 8; ++k) x[k] = buf[k * 64 + L];
+    wave_sync();
+    inv_pass3_store(x, ln, buf, L);
+    wave_sync();
+    inv_pass2(x, buf, L);
+    wave_sync();
+    inv_pass2_store(x, buf, L);
+    wave_sync();
+    inv_pass1(x, ln, buf, L);
+}
+
+// ------------------------------------------------------------------------------------------
+// Bootstrapping key -> transform domain.  One wave per (sample row, component, limb).
+// bk_raw [n][4][2][1024] uint32  ->  bk_fft [n][4][o = 2*component + limb][512] complex.
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(64) void bk_to_spectrum_kernel(const uint32_t *__restrict__ bk_raw,
+                                                            double2 *__restrict__ bk_fft,
+                                                            const double2 *__restrict__ tables) {
+    __shared__ double2 buf[kBufWords];
+    const int L = threadIdx.x;
+    const int limb = blockIdx.x & 1;
+    const size_t poly = blockIdx.x >> 1;           // (i * 4 + r) * 2 + c
+    const int c = (int)(poly & 1);
+    const size_t row = poly >> 1;                  // i * 4 + r
+    const uint32_t *src = bk_raw + poly * kN;
+    Lane ln;
+    lane_init(ln, tables, L);
+    double2 x[8];
+#pragma unroll
+    for (int m = 0; m < 8; ++m) {
+        const int j = L + 64 * m;
+        int32_t v[2];
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const uint32_t w = src[j + h * kHalf];
+            const int32_t lo = (int16_t)(w & 0xFFFFu);
+            const int32_t hi = (int16_t)(((w - (uint32_t)lo) >> 16) & 0xFFFFu);
+            v[h] = limb ? hi : lo;
+        }
+        x[m] = cmul(make_double2((double)v[0], (double)v[1]), ln.twist[m]);
+    }
+    forward_to_slots(x, ln, buf, L);
+    wave_sync();
+    double2 *dst = bk_fft + (row * 4 + (size_t)(c * 2 + limb)) * kHalf;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) dst[k * 64 + L] = buf[k * 64 + L];
+}
+
+// ------------------------------------------------------------------------------------------
+// Blind rotation of B gates per workgroup, 256 threads (4 waves) per gate.
+//   prologue  c = (0, kappa) + m (s0 c0 + s1 c1); abar_j = round(c_j * 2N / 2^32); ACC = (0, X^-bbar v)
+//   n steps   D = X^abar_i ACC - ACC; 4 digit polynomials -> 4 forward FFTs (wave r);
+//             products with the transform-domain key row (all threads, one key load shared by the
+//             B gates); 4 inverse FFTs (wave o = component, limb); ACC += rounded results
+//   epilogue  sample extraction of coefficient 0 -> ext[gate][1025]
+// ------------------------------------------------------------------------------------------
+struct GateLds {
+    double2 spec[4][kBufWords];   // per wave: FFT scratch, then spectrum / product in slot order
+    uint32_t acc[2][kN];          // accumulator: mask, body
+    uint16_t bar[1032];           // abar_0 .. abar_{n-1}, bbar
+};
+
+__device__ __forceinline__ void gate_constants(int op, uint32_t &kappa, uint32_t &mult) {
+    switch (op) {
+    case TFHE_NAND: kappa = kEighth;          mult = 0xFFFFFFFFu; break;
+    case TFHE_AND:  kappa = 0u - kEighth;     mult = 1u;          break;
+    case TFHE_OR:   kappa = kEighth;          mult = 1u;          break;
+    case TFHE_NOR:  kappa = 0u - kEighth;     mult = 0xFFFFFFFFu; break;
+    case TFHE_XOR:  kappa = 2u * kEighth;     mult = 2u;          break;
+    default:        kappa = 0u - 2u * kEighth; mult = 0xFFFFFFFEu; break;   // XNOR
+    }
+}
+
+template <int B>
+__global__ __launch_bounds__(kThreadsPerGate *B) void blind_rotate_kernel(BlindRotateArgs a) {
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+    GateLds *lds = reinterpret_cast<GateLds *>(lds_raw);
+
+    const int tid = threadIdx.x;
+    const int g = tid >> 8;                // gate slot in this workgroup
+    const int lt = tid & 255;              // thread within the gate
+    const int wv = lt >> 6;                // wave within the gate
+    const int L = tid & 63;
+    GateLds &my = lds[g];
+    const size_t gi = (size_t)blockIdx.x * B + g;
+    const bool live = gi < a.count;
+
+    Lane ln;
+    lane_init(ln, a.tables, L);
+
+    // ---- prologue ----
+    {
+        int op = a.uniform_op;
+        size_t i0 = gi, i1 = gi;
+        uint32_t s0 = 1u, s1 = 1u;
+        if (live && a.recs) {
+            const tfhe_gate_rec r = a.recs[gi];
+            op = r.op; i0 = (size_t)r.in0; i1 = (size_t)r.in1;
+            s0 = r.neg0 ? 0xFFFFFFFFu : 1u; s1 = r.neg1 ? 0xFFFFFFFFu : 1u;
+        }
+        uint32_t kappa, mult;
+        gate_constants(op, kappa, mult);
+        const size_t w = (size_t)a.n + 1;
+        for (int j = lt; j <= a.n; j += kThreadsPerGate) {
+            uint32_t c = 0;
+            if (live) {
+                c = mult * (s0 * a.in0[i0 * w + j] + s1 * a.in1[i1 * w + j]);
+                if (j == a.n) c += kappa;
+            }
+            my.bar[j] = (uint16_t)(((c + (1u << 20)) >> 21) & 2047u);
+        }
+    }
+    __syncthreads();
+    {
+        const int bbar = my.bar[a.n];
+        const int bb = bbar & (kN - 1);
+        const uint32_t first = bbar < kN ? kEighth : 0u - kEighth;   // X^-bbar v, closed form
+        for (int j = lt; j < kN; j += kThreadsPerGate) {
+            my.acc[0][j] = 0;
+            my.acc[1][j] = j < kN - bb ? first : 0u - first;
+        }
+    }
+    __syncthreads();
+
+    const int comp = wv >> 1;                   // forward: component of D; inverse: component of ACC
+    const int sel = wv & 1;                     // forward: digit index; inverse: limb
+    const int dshift = 32 - a.bgbit * (sel + 1);
+    const uint32_t dmask = (1u << a.bgbit) - 1u;
+    const int dhalf = 1 << (a.bgbit - 1);
+    const uint32_t doffset = ((uint32_t)dhalf << (32 - a.bgbit)) + ((uint32_t)dhalf << (32 - 2 * a.bgbit)) +
+                             (1u << (31 - 2 * a.bgbit));
+    double worst = 0.0;
+
+    for (int i = 0; i < a.n; ++i) {
+        // ---- rotate, subtract, decompose, fold and twist ----
+        const int abar = my.bar[i];
+        const uint32_t *acc = my.acc[comp];
+        double2 x[8];
+#pragma unroll
+        for (int m = 0; m < 8; ++m) {
+            int32_t dig[2];
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int j = L + 64 * m + h * kHalf;
+                const int src = (j - abar) & (2 * kN - 1);
+                const uint32_t p = acc[src & (kN - 1)];
+                const uint32_t d = (src < kN ? p : 0u - p) - acc[j];
+                dig[h] = (int32_t)(((d + doffset) >> dshift) & dmask) - dhalf;
+            }
+            x[m] = cmul(make_double2((double)dig[0], (double)dig[1]), ln.twist[m]);
+        }
+        forward_to_slots(x, ln, my.spec[wv], L);
+        __syncthreads();
+
+        // ---- products with the key row: thread <-> slot, all gates of the workgroup ----
+        {
+            const double2 *key = a.bk_fft + (size_t)i * 16 * kHalf;
+            for (int s = tid; s < kHalf; s += kThreadsPerGate * B) {
+                double2 k[4][4];
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+#pragma unroll
+                    for (int o = 0; o < 4; ++o) k[r][o] = key[(r * 4 + o) * kHalf + s];
+#pragma unroll
+                for (int q = 0; q < B; ++q) {
+                    double2 d[4], y[4];
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) d[r] = lds[q].spec[r][s];
+#pragma unroll
+                    for (int o = 0; o < 4; ++o) {
+                        y[o] = cmul(d[0], k[0][o]);
+#pragma unroll
+                        for (int r = 1; r < 4; ++r) {
+                            y[o].x += d[r].x * k[r][o].x - d[r].y * k[r][o].y;
+                            y[o].y += d[r].x * k[r][o].y + d[r].y * k[r][o].x;
+                        }
+                    }
+#pragma unroll
+                    for (int o = 0; o < 4; ++o) lds[q].spec[o][s] = y[o];
+                }
+            }
+        }
+        __syncthreads();
+
+        // ---- inverse transform, exact rounding, accumulate ----
+        inverse_from_slots(x, ln, my.spec[wv], L);
+#pragma unroll
+        for (int m = 0; m < 8; ++m) {
+            const double2 v = cmulc(x[m], ln.twist[m]);
+            const double part[2] = {v.x * (1.0 / 512.0), v.y * (1.0 / 512.0)};
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                // adding 1.5 * 2^52 leaves round-to-nearest(part) mod 2^32 in the low word
+                const double shifted = part[h] + 6755399441055744.0;
+                uint32_t r = (uint32_t)__double2loint(shifted);
+                if (a.margin) worst = fmax(worst, fabs(part[h] - (shifted - 6755399441055744.0)));
+                if (sel) r <<= 16;
+                atomicAdd(&my.acc[comp][L + 64 * m + h * kHalf], r);
+            }
+        }
+        __syncthreads();
+    }
+
+    // ---- epilogue: the constant coefficient as an LWE sample under the ring key ----
+    if (live) {
+        uint32_t *ext = a.ext + gi * (size_t)(kN + 1);
+        for (int j = lt; j < kN; j += kThreadsPerGate) ext[j] = j == 0 ? my.acc[0][0] : 0u - my.acc[0][kN - j];
+        if (lt == 0) ext[kN] = my.acc[1][0];
+    }
+    if (a.margin) {
+        // non-negative doubles order like their bit patterns
+        atomicMax(reinterpret_cast<unsigned long long *>(a.margin),
+                  (unsigned long long)__double_as_longlong(worst));
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Key switch, one workgroup per gate:  out = (0, b') - sum_{i,j} KSK[i][j][digit_ij]
+// over the t base-2^basebit digits of the rounded mask words; digit 0 reads the zero row
+// appended to the key so that all loads of one mask word can be in flight together.
+// ------------------------------------------------------------------------------------------
+template <int T>
+__global__ __launch_bounds__(256) void key_switch_kernel(KeySwitchArgs a) {
+    __shared__ uint32_t ext[kN + 1];
+    const int tid = threadIdx.x;
+    const size_t gi = blockIdx.x;
+    const uint32_t *src = a.ext + gi * (size_t)(kN + 1);
+    for (int j = tid; j <= kN; j += 256) ext[j] = src[j];
+    __syncthreads();
+
+    const int words = a.n + 1;
+    constexpr int kMaxPerThread = 5;              // ceil(1025 / 256)
+    uint32_t acc[kMaxPerThread];
+#pragma unroll
+    for (int q = 0; q < kMaxPerThread; ++q) {
+        const int w = tid + 256 * q;
+        acc[q] = w == a.n ? ext[kN] : 0u;
+    }
+    const int values = (1 << a.basebit) - 1;
+    const uint32_t round = 1u << (31 - T * a.basebit);
+    const size_t zero_row = (size_t)kN * T * values;
+    const int per_thread = (words + 255) >> 8;
+    for (int i = 0; i < kN; ++i) {
+        const uint32_t ai = ext[i] + round;
+        const uint32_t *rows[T];
+#pragma unroll
+        for (int j = 0; j < T; ++j) {
+            const uint32_t v = (ai >> (32 - a.basebit * (j + 1))) & (uint32_t)values;
+            const size_t row = v ? ((size_t)i * T + j) * values + (v - 1) : zero_row;
+            rows[j] = a.ksk + row * (size_t)words;
+        }
+        for (int q = 0; q < per_thread; ++q) {
+            const int w = tid + 256 * q;
+            if (w < words) {
+                uint32_t part[T];
+#pragma unroll
+                for (int j = 0; j < T; ++j) part[j] = rows[j][w];
+                uint32_t sum = 0;
+#pragma unroll
+                for (int j = 0; j < T; ++j) sum += part[j];
+                acc[q] -= sum;
+            }
+        }
+    }
+    const size_t out_index = a.recs ? (size_t)a.recs[gi].out : gi;
+    uint32_t *out = a.out + out_index * (size_t)words;
+#pragma unroll
+    for (int q = 0; q < kMaxPerThread; ++q) {
+        const int w = tid + 256 * q;
+        if (w < words) out[w] = acc[q];
+    }
+}
+
+// out[k] = +-wires[ref.wire]  or the noiseless sample of the constant bit
+__global__ void gather_outputs_kernel(const uint32_t *wires, const tfhe_out_ref *refs, uint32_t *out,
+                                      size_t count, int words) {
+    const size_t k = blockIdx.x;
+    if (k >= count) return;
+    const tfhe_out_ref r = refs[k];
+    for (int w = threadIdx.x; w < words; w += blockDim.x) {
+        uint32_t v;
+        if (r.wire >= 0) {
+            v = wires[(size_t)r.wire * words + w];
+            if (r.value) v = 0u - v;
+        } else {
+            v = w == words - 1 ? (r.value ? kEighth : 0u - kEighth) : 0u;
+        }
+        out[k * (size_t)words + w] = v;
+    }
+}
+
+__global__ void fill_trivial_kernel(uint32_t *ct, int words, uint32_t body) {
+    for (int w = threadIdx.x; w < words; w += blockDim.x) ct[w] = w == words - 1 ? body : 0u;
+}
+
+}  // namespace
+
+size_t blind_rotate_lds_bytes(int gates_per_group) { return sizeof(GateLds) * (size_t)gates_per_group; }
+
+int launch_bk_to_spectrum(const uint32_t *bk_raw, double2 *bk_fft, const double2 *tables, int n,
+                          hipStream_t stream) {
+    const unsigned blocks = (unsigned)n * 4 * 2 * 2;
+    hipLaunchKernelGGL(bk_to_spectrum_kernel, dim3(blocks), dim3(64), 0, stream, bk_raw, bk_fft, tables);
+    TFHE_HIP(hipGetLastError());
+    return TFHE_OK;
+}
+
+template <int B>
+static int launch_br(const BlindRotateArgs &a, hipStream_t stream) {
+    const size_t lds = blind_rotate_lds_bytes(B);
+    static bool configured = false;
+    if (!configured) {
+        TFHE_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&blind_rotate_kernel<B>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        configured = true;
+    }
+    const unsigned blocks = (unsigned)((a.count + B - 1) / B);
+    hipLaunchKernelGGL(blind_rotate_kernel<B>, dim3(blocks), dim3(kThreadsPerGate * B), lds, stream, a);
+    TFHE_HIP(hipGetLastError());
+    return TFHE_OK;
+}
+
+int launch_blind_rotate(const BlindRotateArgs &a, int gates_per_group, hipStream_t stream) {
+    if (a.count == 0) return TFHE_OK;
+    switch (gates_per_group) {
+    case 1: return launch_br<1>(a, stream);
+    case 2: return launch_br<2>(a, stream);
+    case 3: return launch_br<3>(a, stream);
+    default: return set_error(TFHE_E_PARAM, "unsupported gates per workgroup %d", gates_per_group);
+    }
+}
+
+int launch_key_switch(const KeySwitchArgs &a, hipStream_t stream) {
+    if (a.count == 0) return TFHE_OK;
+    const dim3 grid((unsigned)a.count), block(256);
+    switch (a.t) {
+#define KS_CASE(T) case T: hipLaunchKernelGGL(key_switch_kernel<T>, grid, block, 0, stream, a); break;
+        KS_CASE(1) KS_CASE(2) KS_CASE(3) KS_CASE(4) KS_CASE(5) KS_CASE(6) KS_CASE(7) KS_CASE(8)
+        KS_CASE(9) KS_CASE(10) KS_CASE(11) KS_CASE(12)
+#undef KS_CASE
+    default: return set_error(TFHE_E_PARAM, "unsupported key-switch digit count %d", a.t);
+    }
+    TFHE_HIP(hipGetLastError());
+    return TFHE_OK;
+}
+
+int launch_gather_outputs(const uint32_t *wires, const tfhe_out_ref *refs, uint32_t *out, size_t count,
+                          int words, hipStream_t stream) {
+    if (count == 0) return TFHE_OK;
+    hipLaunchKernelGGL(gather_outputs_kernel, dim3((unsigned)count), dim3(256), 0, stream, wires, refs, out,
+                       count, words);
+    TFHE_HIP(hipGetLastError());
+    return TFHE_OK;
+}
+
+int launch_fill_trivial(uint32_t *ct, int words, int bit, hipStream_t stream) {
+    hipLaunchKernelGGL(fill_trivial_kernel, dim3(1), dim3(256), 0, stream, ct, words,
+                       bit ? kEighth : 0u - kEighth);
+    TFHE_HIP(hipGetLastError());
+    return TFHE_OK;
+}
+
+}  // namespace tfhe

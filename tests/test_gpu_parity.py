@@ -1,0 +1,161 @@
+"""GPU parity: ciphertext bytes produced by the HIP library (through its C ABI) against the CPU
+oracle, on the same seeded keys and inputs.  All arithmetic is exact modulo 2^32, so the bar is
+bit-for-bit equality; decrypted bits are also checked against plain truth tables / integer layers.
+"""
+import itertools
+
+import numpy as np
+import pytest
+
+import workloads
+from oracle import circuits as cc
+
+pytestmark = pytest.mark.gpu
+
+TRUTH = {"NAND": lambda a, b: 1 - (a & b), "AND": lambda a, b: a & b, "OR": lambda a, b: a | b,
+         "NOR": lambda a, b: 1 - (a | b), "XOR": lambda a, b: a ^ b, "XNOR": lambda a, b: 1 - (a ^ b)}
+OPNAMES = ["NAND", "AND", "OR", "NOR", "XOR", "XNOR"]
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    import paper_1806_03461_amd as T
+    sk, ck = T.tfhe_keygen(T.default_params(), workloads.KEY_SEED)
+    T.tfhe_cloud_key_upload(ck)
+    return T, sk, ck
+
+
+def run_batch(T, ck, op, cta, ctb):
+    import torch
+    a, b = T.to_device(cta), T.to_device(ctb)
+    out = torch.empty_like(a)
+    T.tfhe_gate_batch(ck, op, a, b, out, a.shape[0])
+    torch.cuda.synchronize()
+    return T.to_host(out)
+
+
+def oracle_batch(keys, op, cta, ctb, threads=16):
+    n1 = cta.shape[1]
+    cnt = cta.shape[0]
+    wires = np.zeros((3 * cnt, n1), np.uint32)
+    wires[:cnt], wires[cnt:2 * cnt] = cta, ctb
+    recs = np.array([(cc.OP[op], 0, 0, 0, i, cnt + i, 2 * cnt + i) for i in range(cnt)], dtype=cc.GATE_DTYPE)
+    keys.gate_batch(recs, wires, threads)
+    return wires[2 * cnt:]
+
+
+def test_cfg1_sixteen_gates_bit_exact(gpu, real_keys):
+    T, sk, ck = gpu
+    c = workloads.cfg1()
+    cta = T.tfhe_encrypt(sk, c["enc_seed"], c["a"])
+    ctb = T.tfhe_encrypt(sk, c["enc_seed"] + 1, c["b"])
+    assert np.array_equal(cta, real_keys.encrypt(c["a"], c["enc_seed"]))
+    got = np.concatenate([run_batch(T, ck, "NAND", cta[:8], ctb[:8]), run_batch(T, ck, "XNOR", cta[8:], ctb[8:])])
+    want = np.concatenate([oracle_batch(real_keys, "NAND", cta[:8], ctb[:8]),
+                           oracle_batch(real_keys, "XNOR", cta[8:], ctb[8:])])
+    assert np.array_equal(got, want)
+    bits = T.tfhe_decrypt(sk, got)
+    plain = [TRUTH[o](int(a), int(b)) for o, a, b in zip(c["ops"], c["a"], c["b"])]
+    assert list(bits) == plain
+
+
+@pytest.mark.parametrize("op", OPNAMES)
+def test_every_gate_kind_ragged_batch(gpu, real_keys, op):
+    """7 gates: not a multiple of any gates-per-workgroup setting; covers all four input pairs."""
+    T, sk, ck = gpu
+    a = np.array([0, 0, 1, 1, 1, 0, 1], np.uint8)
+    b = np.array([0, 1, 0, 1, 1, 0, 0], np.uint8)
+    cta, ctb = T.tfhe_encrypt(sk, 11, a), T.tfhe_encrypt(sk, 12, b)
+    got = run_batch(T, ck, op, cta, ctb)
+    assert np.array_equal(got, oracle_batch(real_keys, op, cta, ctb))
+    assert list(T.tfhe_decrypt(sk, got)) == [TRUTH[op](int(x), int(y)) for x, y in zip(a, b)]
+
+
+def test_empty_and_in_place_batches(gpu, real_keys):
+    import torch
+    T, sk, ck = gpu
+    T.tfhe_gate_batch(ck, "AND", 0, 0, 0, 0)                       # count 0: no-op, pointers unused
+    a = np.array([1, 0, 1], np.uint8)
+    cta, ctb = T.tfhe_encrypt(sk, 21, a), T.tfhe_encrypt(sk, 22, a[::-1].copy())
+    da, db = T.to_device(cta), T.to_device(ctb)
+    T.tfhe_gate_batch(ck, "OR", da, db, da, 3)                     # out aliases a
+    torch.cuda.synchronize()
+    assert np.array_equal(T.to_host(da), oracle_batch(real_keys, "OR", cta, ctb))
+
+
+def test_mixed_gate_stream_with_negated_inputs(gpu, real_keys):
+    """A small layer through bnn_dense_lower + tfhe_gate_stream: every wire equals the oracle's
+    evaluation of the same records, and the oracle's own lowering gives the same output bytes."""
+    import torch
+    T, sk, ck = gpu
+    rng = np.random.default_rng(5)
+    d, p = 14, 3
+    W = rng.choice(np.array([-1, 0, 1], np.int8), (p, d), p=[0.45, 0.1, 0.45])
+    Tt = np.array([4, 7, 6], np.int32)
+    x = rng.integers(0, 2, d).astype(np.uint8)
+    ctx = T.tfhe_encrypt(sk, 31, x)
+    gates, outs, nw = T.bnn_dense_lower(d, W, Tt, p)
+    wires = np.zeros((nw, 501), np.uint32)
+    wires[:d] = ctx
+    wires[d], wires[d + 1] = T.tfhe_trivial(T.default_params(), 0), T.tfhe_trivial(T.default_params(), 1)
+    dev = T.to_device(wires)
+    T.tfhe_gate_stream(ck, gates, dev, nw)
+    torch.cuda.synchronize()
+    got = T.to_host(dev)
+    want = wires.copy()
+    real_keys.run_gates(gates, want, threads=16)
+    assert np.array_equal(got, want)
+    # the layer entry point, against the oracle's independent circuit builder
+    out = torch.empty((p, 501), dtype=torch.int32, device="cuda")
+    T.bnn_dense_encrypted(ck, T.to_device(ctx), d, W, Tt, p, out)
+    torch.cuda.synchronize()
+    cir, o = cc.dense_layer(d, W, Tt)
+    ref, _ = cc.eval_encrypted(real_keys, cir, ctx, o, threads=16)
+    assert np.array_equal(T.to_host(out), ref)
+    assert np.array_equal(T.tfhe_decrypt(sk, T.to_host(out)), cc.dense_plain(x, W, Tt))
+
+
+def test_large_batch_truth_tables_and_sampled_parity(gpu, real_keys):
+    """4099 gates (several workgroups per CU plus a ragged tail): all outputs decrypt to the truth
+    table; 24 sampled outputs are compared byte for byte with the oracle."""
+    T, sk, ck = gpu
+    rng = np.random.default_rng(7)
+    cnt = 4099
+    a, b = rng.integers(0, 2, cnt).astype(np.uint8), rng.integers(0, 2, cnt).astype(np.uint8)
+    cta, ctb = T.tfhe_encrypt(sk, 41, a), T.tfhe_encrypt(sk, 42, b)
+    for op in ("NAND", "XOR"):
+        got = run_batch(T, ck, op, cta, ctb)
+        assert np.array_equal(T.tfhe_decrypt(sk, got), np.array([TRUTH[op](int(x), int(y)) for x, y in zip(a, b)], np.uint8))
+        idx = np.concatenate([rng.integers(0, cnt, 20), [0, 1, cnt - 2, cnt - 1]])
+        assert np.array_equal(got[idx], oracle_batch(real_keys, op, cta[idx], ctb[idx]))
+
+
+def test_rounding_margin_of_the_split_integer_products(gpu):
+    """The transform-domain products are rounded to integers; the distance of the raw values from
+    an integer must stay far below 1/2 for the rounding to be exact."""
+    T, sk, ck = gpu
+    rng = np.random.default_rng(9)
+    a = rng.integers(0, 2, 64).astype(np.uint8)
+    cta, ctb = T.tfhe_encrypt(sk, 51, a), T.tfhe_encrypt(sk, 52, a[::-1].copy())
+    T.tfhe_rounding_margin_enable(ck, True)
+    try:
+        run_batch(T, ck, "XNOR", cta, ctb)
+        worst = T.tfhe_rounding_margin_read(ck)
+    finally:
+        T.tfhe_rounding_margin_enable(ck, False)
+    assert 0 < worst < 1e-3, worst
+
+
+def test_bad_gate_records_are_rejected(gpu):
+    import torch
+    T, sk, ck = gpu
+    wires = torch.zeros((4, 501), dtype=torch.int32, device="cuda")
+    def rec(op, i0, i1, out):
+        return np.array([(op, 0, 0, 0, i0, i1, out)], dtype=T.GATE_DTYPE)
+    for bad in (rec(9, 0, 1, 2), rec(1, 0, 7, 2), rec(1, 0, 1, -1),
+                np.concatenate([rec(1, 0, 1, 2), rec(1, 0, 1, 2)]),       # wire written twice
+                np.concatenate([rec(1, 3, 1, 2), rec(1, 0, 1, 3)])):      # reads a later record's output
+        with pytest.raises(T.TfheError):
+            T.tfhe_gate_stream(ck, bad, wires, 4)

@@ -1,0 +1,156 @@
+"""CPU-side checks of the GPU library: it loads, exports every declared symbol, and its host
+logic (key generation, encryption, decryption, circuit lowering, argument checking) agrees
+with the independent oracle.  No kernel is launched here."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_1806_03461_amd as T
+import workloads
+from oracle import circuits as cc
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "tfhe_mi355x.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b((?:tfhe|bnn)_[a-z_]+)\s*\(", header))
+    assert {"tfhe_keygen", "tfhe_encrypt", "tfhe_decrypt", "tfhe_gate_batch", "tfhe_gate_stream",
+            "bnn_dense_encrypted", "bnn_conv_encrypted"} <= declared
+    L = T.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+    assert declared == set(T.EXPORTS)
+
+
+@pytest.fixture(scope="module")
+def small():
+    P = T.Params(24, 64, 1, 2, 10, 8, 2, -15, -25)
+    return P, T.tfhe_keygen(P, 4242)
+
+
+def test_keygen_matches_oracle_bit_for_bit(orc, small):
+    P, (sk, ck) = small
+    K = orc.Keys(orc.Params(*[getattr(P, f) for f, _ in P._fields_]), 4242)
+    assert np.array_equal(T.tfhe_export_key(sk, T.KEY_LWE_SK), K.lwe_sk)
+    assert np.array_equal(T.tfhe_export_key(sk, T.KEY_TRLWE_SK), K.trlwe_sk)
+    assert np.array_equal(T.tfhe_export_key(ck, T.KEY_BK_RAW), K.bk)
+    assert np.array_equal(T.tfhe_export_key(ck, T.KEY_KSK_RAW), K.ksk)
+
+
+def test_keygen_matches_oracle_at_benchmark_parameters(real_keys):
+    sk, ck = T.tfhe_keygen(T.default_params(), workloads.KEY_SEED)
+    assert np.array_equal(T.tfhe_export_key(sk, T.KEY_LWE_SK), real_keys.lwe_sk)
+    assert np.array_equal(T.tfhe_export_key(sk, T.KEY_TRLWE_SK), real_keys.trlwe_sk)
+    assert np.array_equal(T.tfhe_export_key(ck, T.KEY_BK_RAW), real_keys.bk)
+    assert np.array_equal(T.tfhe_export_key(ck, T.KEY_KSK_RAW), real_keys.ksk)
+
+
+def test_encrypt_decrypt_match_oracle(real_keys):
+    sk, _ = T.tfhe_keygen(T.default_params(), workloads.KEY_SEED)
+    bits = np.random.default_rng(1).integers(0, 2, 300).astype(np.uint8)
+    ct = T.tfhe_encrypt(sk, 99, bits)
+    assert np.array_equal(ct, real_keys.encrypt(bits, 99))
+    assert np.array_equal(T.tfhe_decrypt(sk, ct), bits)
+    noisy = ct.copy()
+    noisy[:, -1] += np.uint32(1 << 27)
+    assert np.array_equal(T.tfhe_decrypt(sk, noisy), real_keys.decrypt(noisy))
+    for b in (0, 1):
+        assert np.array_equal(T.tfhe_trivial(T.default_params(), b), real_keys.trivial(b))
+    assert T.tfhe_encrypt(sk, 1, np.zeros(0, np.uint8)).shape == (0, 501)
+
+
+_INTERN = {}
+
+
+def canonical(gates, outs, n_wires, n_inputs):
+    """A circuit as one structural id per output: independent of wire numbering and of the
+    order of a gate's two operands.  Equal sub-circuits get equal ids (hash-consing in a table
+    shared by both sides of a comparison)."""
+    ident = {}
+    for w in range(n_inputs + 2):
+        ident[w] = _INTERN.setdefault(("in", w), len(_INTERN))
+    for g in gates:                                     # topological order
+        a = (ident[int(g["in0"])], int(g["neg0"]))
+        b = (ident[int(g["in1"])], int(g["neg1"]))
+        key = (int(g["op"]),) + tuple(sorted((a, b)))
+        ident[int(g["out"])] = _INTERN.setdefault(key, len(_INTERN))
+    return [("const", int(v)) if w < 0 else (ident[int(w)], int(v)) for w, v in outs]
+
+
+def oracle_outs(outs):
+    res = []
+    for lit in outs:
+        if lit is cc.CONST0:
+            res.append((-1, 0))
+        elif lit is cc.CONST1:
+            res.append((-1, 1))
+        else:
+            res.append(lit)
+    return res
+
+
+@pytest.mark.parametrize("d,p,sparse,with_T", [(5, 3, False, True), (33, 4, True, True), (64, 2, False, False),
+                                               (144, 3, False, True), (100, 5, True, False)])
+def test_dense_lowering_is_the_oracle_circuit(d, p, sparse, with_T):
+    rng = np.random.default_rng(d + p)
+    W = (2 * rng.integers(0, 2, (p, d)) - 1).astype(np.int8)
+    if sparse:
+        W[rng.random((p, d)) < 0.5] = 0
+    Tt = rng.integers(-1, d + 2, p).astype(np.int32) if with_T else None
+    gates, outs, nw = T.bnn_dense_lower(d, W, Tt, p, 10)
+    cir, o = cc.dense_layer(d, W, Tt, 10)
+    assert nw == cir.n_wires and len(gates) == len(cir.gates)
+    mine = canonical(gates, [(int(r["wire"]), int(r["value"])) for r in outs], nw, d)
+    theirs = canonical(cir.gate_array(), oracle_outs(o), cir.n_wires, d)
+    assert mine == theirs
+
+
+def test_conv_lowering_is_the_oracle_circuit():
+    c4 = workloads.cfg4(C=2, H=4, Wd=5, O=3)
+    gates, outs, nw = T.bnn_conv_lower(2, 4, 5, c4["K"], c4["T"] // 8, 1, 1)
+    cir, o = cc.conv_layer(2, 4, 5, c4["K"], c4["T"] // 8, 1, 1)
+    assert nw == cir.n_wires and len(outs) == 3 * 4 * 5
+    mine = canonical(gates, [(int(r["wire"]), int(r["value"])) for r in outs], nw, 40)
+    assert mine == canonical(cir.gate_array(), oracle_outs(o), cir.n_wires, 40)
+    gates, outs, nw = T.bnn_conv_lower(2, 4, 5, c4["K"], c4["T"] // 8, 2, 0)
+    cir, o = cc.conv_layer(2, 4, 5, c4["K"], c4["T"] // 8, 2, 0)
+    assert canonical(gates, [(int(r["wire"]), int(r["value"])) for r in outs], nw, 40) == \
+        canonical(cir.gate_array(), oracle_outs(o), cir.n_wires, 40)
+
+
+def test_benchmark_layer_lowering_counts():
+    c3 = workloads.cfg3()
+    gates, outs, nw = T.bnn_dense_lower(784, c3["W"], c3["T"], 512)
+    assert len(outs) == 512 and 512 * 5435 <= len(gates) <= 512 * 5443
+    assert nw == 784 + 2 + len(gates)
+
+
+def test_argument_errors_are_reported_not_thrown():
+    L = T.lib()
+    bad = T.Params(500, 1000, 1, 2, 10, 8, 2, -15, -25)          # N not a power of two
+    sk, ck = C.c_void_p(), C.c_void_p()
+    assert L.tfhe_keygen(C.byref(bad), 1, C.byref(sk), C.byref(ck)) == -2
+    assert b"power of two" in L.tfhe_last_error()
+    bad = T.Params(0, 1024, 1, 2, 10, 8, 2, -15, -25)
+    assert L.tfhe_keygen(C.byref(bad), 1, C.byref(sk), C.byref(ck)) == -2
+    assert L.tfhe_keygen(None, 1, C.byref(sk), C.byref(ck)) == -1
+    ok = T.Params(8, 16, 1, 2, 10, 8, 2, -15, -25)
+    assert L.tfhe_keygen(C.byref(ok), 1, None, None) == -1
+    assert L.tfhe_encrypt(None, 1, None, 0, None) == -1
+    with pytest.raises(T.TfheError):
+        T.bnn_dense_lower(4, np.array([[2, 0, 1, 1]], np.int8), np.array([1], np.int32), 1)
+    with pytest.raises(T.TfheError):
+        T.bnn_dense_lower(300, np.ones((1, 300), np.int8), None, 1, out_bits=8)   # popcount needs 9 bits
+    # parameters the kernels do not support are refused before any device work
+    sk2, ck2 = T.tfhe_keygen(ok, 3)
+    with pytest.raises(T.TfheError) as e:
+        T.tfhe_gate_batch(ck2, "AND", 0, 0, 0, 0, stream=0)
+    assert e.value.code == -2
+    ln = C.c_size_t(3)
+    buf = (C.c_uint32 * 1)()
+    assert L.tfhe_export_key(sk2.handle, T.KEY_LWE_SK, buf, C.byref(ln)) == -3 and ln.value == 32
