@@ -1,0 +1,169 @@
+"""Benchmark of the encrypted-BNN hot path on one MI355X.
+
+A step is one encrypted fully connected layer 784 -> 512 (benchmark configuration 3): host
+lowering of the layer to its gate circuit, depth-sorted batching, and every gate's blind
+rotation and key switch on the GPU, with keys and input ciphertexts already resident in HBM.
+The headline value is bootstrapped gates per second over the timed steps; ms_per_step is the
+layer latency.  The line also carries the roofline of the dominant kernel (blind rotation,
+measured with HIP events on the stream it runs on) and the CPU oracle timed on a bounded sample
+of the same gate stream.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3|cfg2|flat] [--no-cpu]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+# Algorithmic double-precision work of one bootstrapped gate on this path (n = 500 steps):
+# per step 8 complex 512-point FFTs at the conventional 5 N log2 N flops, 8 x 512 complex
+# twist / untwist multiplications (6 flops), 16 x 512 complex multiply-accumulates (8 flops).
+FLOPS_PER_STEP = 8 * 5 * 512 * 9 + 8 * 512 * 6 + 16 * 512 * 8
+FP64_VECTOR_PEAK_TFLOPS = 78.6
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="cfg3", choices=["cfg3", "cfg2", "flat"])
+    ap.add_argument("--flat-count", type=int, default=65536)
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--cpu-gates", type=int, default=512, help="gates in the oracle sample")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only; --gpus must be 1 "
+                 "(sharding across GPUs is described in DESIGN.md, not built)")
+
+    import torch
+    import paper_1806_03461_amd as T
+    import workloads
+
+    assert torch.cuda.is_available(), "bench.py needs the MI355X"
+    torch.cuda.set_device(0)
+    P = T.default_params()
+    sk, ck = T.tfhe_keygen(P, workloads.KEY_SEED)
+    T.tfhe_cloud_key_upload(ck)
+    words = P.n + 1
+
+    if args.workload == "cfg3":
+        c = workloads.cfg3()
+        name = "cfg3: encrypted FC 784->512, +-1 weights, thresholds in [300,484]"
+    elif args.workload == "cfg2":
+        c = workloads.cfg2()
+        name = "cfg2: one encrypted neuron, 256 inputs"
+    else:
+        c = None
+        name = f"flat: {args.flat_count} independent NAND gates"
+
+    if c is not None:
+        p, d = c["W"].shape
+        x = T.to_device(T.tfhe_encrypt(sk, c["enc_seed"], c["x"]))
+        out = torch.empty((p, words), dtype=torch.int32, device="cuda")
+        gates_host, _, _ = T.bnn_dense_lower(d, c["W"], c["T"], p)
+        gates_per_step = len(gates_host)
+
+        def step():
+            T.bnn_dense_encrypted(ck, x, d, c["W"], c["T"], p, out)
+    else:
+        rng = np.random.default_rng(0)
+        cnt = args.flat_count
+        a = rng.integers(0, 2, cnt).astype(np.uint8)
+        b = rng.integers(0, 2, cnt).astype(np.uint8)
+        da, db = T.to_device(T.tfhe_encrypt(sk, 1, a)), T.to_device(T.tfhe_encrypt(sk, 2, b))
+        out = torch.empty_like(da)
+        gates_per_step = cnt
+
+        def step():
+            T.tfhe_gate_batch(ck, "NAND", da, db, out, cnt)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    T.tfhe_profile_enable(ck, True)
+    T.tfhe_profile_read(ck, reset=True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    prof = T.tfhe_profile_read(ck, reset=True)
+    T.tfhe_profile_enable(ck, False)
+
+    elapsed = t1 - t0
+    total_gates = gates_per_step * args.steps
+    value = total_gates / elapsed
+
+    # correctness of what was timed: decrypt and compare with the plain layer / truth table
+    got = T.tfhe_decrypt(sk, T.to_host(out))
+    if c is not None:
+        xs = 2 * c["x"].astype(np.int64) - 1
+        S = ((c["W"].astype(np.int64) * xs[None, :]) > 0).sum(axis=1)
+        expect = (S >= c["T"]).astype(np.uint8)
+    else:
+        expect = 1 - (a & b)
+    mismatches = int((got != expect).sum())
+
+    # roofline of the dominant kernel: algorithmic flops of the gates of one launch over the
+    # average launch duration, from HIP events recorded around every launch on the call's stream
+    br_launches = max(1, prof["blind_rotate_launches"])
+    br_avg_ms = prof["blind_rotate_ms"] / br_launches
+    gates_per_launch = prof["gates"] / br_launches
+    flops_per_gate = FLOPS_PER_STEP * P.n
+    achieved = flops_per_gate * gates_per_launch / (br_avg_ms * 1e-3) / 1e12 if br_avg_ms > 0 else 0.0
+    roofline = {"bound": "alu", "achieved": round(achieved, 3), "peak": FP64_VECTOR_PEAK_TFLOPS,
+                "unit": "TFLOP/s", "frac": round(achieved / FP64_VECTOR_PEAK_TFLOPS, 4),
+                "traffic": None, "kernel": "blind_rotate_kernel",
+                "avg_launch_ms": round(br_avg_ms, 4), "gates_per_launch": round(gates_per_launch, 1),
+                "flops_per_gate": flops_per_gate,
+                "kernel_ms": {"blind_rotate": round(prof["blind_rotate_ms"], 2),
+                              "key_switch": round(prof["key_switch_ms"], 2)}}
+
+    cpu = None
+    if not args.no_cpu:
+        from oracle import oracle as orc
+        keys = orc.Keys(orc.default_params(), workloads.KEY_SEED)
+        threads = min(16, os.cpu_count() or 1)
+        ng = args.cpu_gates
+        if c is not None:
+            # the first ng gates of the layer's circuit are first-level gates: inputs only
+            sample = np.array(gates_host[:ng], dtype=orc.GATE_DTYPE)
+            nin = d + 2
+            wires = np.zeros((int(sample["out"].max()) + 1, words), np.uint32)
+            wires[:d] = T.to_host(x)
+            wires[d], wires[d + 1] = keys.trivial(0), keys.trivial(1)
+            assert int(max(sample["in0"].max(), sample["in1"].max())) < nin
+            what = f"first {ng} gates of the {args.workload} gate stream"
+        else:
+            ng = min(ng, cnt)
+            sample = np.array([(0, 0, 0, 0, i, ng + i, 2 * ng + i) for i in range(ng)], dtype=orc.GATE_DTYPE)
+            wires = np.zeros((3 * ng, words), np.uint32)
+            wires[:ng], wires[ng:2 * ng] = T.to_host(da)[:ng], T.to_host(db)[:ng]
+            what = f"first {ng} gates of the flat batch"
+        t0 = time.perf_counter()
+        keys.gate_batch(sample, wires, threads)
+        dt = time.perf_counter() - t0
+        cpu = {"value": round(ng / dt, 2), "unit": "gates/s", "cores": threads, "kind": "oracle",
+               "sample": f"{what}, {dt:.1f} s"}
+
+    line = {"metric": "bootstrapped gates/sec (n=500,N=1024) on 1 MI355X; encrypted BNN layer latency",
+            "value": round(value, 1), "unit": "gates/s", "n_gpus": 1, "steps": args.steps,
+            "warmup": args.warmup, "ms_per_step": round(elapsed / args.steps * 1e3, 3),
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64",
+            "data": "synthetic", "config": {"workload": name, "gates_per_step": gates_per_step,
+                                            "decrypt_mismatches": mismatches},
+            "roofline": roofline, "cpu_baseline": cpu}
+    print(json.dumps(line))
+    if mismatches:
+        sys.exit(f"bench.py: {mismatches} outputs decrypt to the wrong bit")
+
+
+if __name__ == "__main__":
+    main()

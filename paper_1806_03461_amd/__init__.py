@@ -125,8 +125,8 @@ class SecretKey:
         self.handle = handle
 
     def __del__(self):
-        if getattr(self, "handle", None):
-            lib().tfhe_free_secret_key(self.handle)
+        if getattr(self, "handle", None) and _lib is not None:
+            _lib.tfhe_free_secret_key(self.handle)
             self.handle = None
 
 
@@ -135,8 +135,8 @@ class CloudKey:
         self.handle = handle
 
     def __del__(self):
-        if getattr(self, "handle", None):
-            lib().tfhe_free_cloud_key(self.handle)
+        if getattr(self, "handle", None) and _lib is not None:
+            _lib.tfhe_free_cloud_key(self.handle)
             self.handle = None
 
 
