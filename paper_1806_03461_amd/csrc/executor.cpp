@@ -83,7 +83,7 @@ int run_batch(tfhe_cloud_key *ck, const tfhe_gate_rec *d_recs, int uniform_op, c
     br.margin = ck->margin ? ck->d_margin : nullptr;
     KeySwitchArgs ks{};
     ks.ext = br.ext; ks.recs = d_recs; ks.out = out; ks.count = count; ks.ksk = ck->d_ksk;
-    ks.n = P.n; ks.t = P.ks_t; ks.basebit = P.ks_basebit;
+    ks.n = P.n; ks.t = P.ks_t; ks.basebit = P.ks_basebit; ks.stride = (P.n + 2) & ~1;
 
     TimedLaunch tl{};
     if (ck->profile) if (int rc = begin_timed(ck, 0, stream, tl)) return rc;
@@ -185,11 +185,13 @@ int tfhe_cloud_key_upload(tfhe_cloud_key *ck) {
     TFHE_HIP(hipMalloc((void **)&ck->d_tables, tables.size() * sizeof(double2)));
     TFHE_HIP(hipMemcpy(ck->d_tables, tables.data(), tables.size() * sizeof(double2), hipMemcpyHostToDevice));
 
-    // key-switching key plus one zero row (what digit 0 reads)
-    const size_t ksk_words = ck->ksk_raw.size(), row = (size_t)P.n + 1;
-    TFHE_HIP(hipMalloc((void **)&ck->d_ksk, (ksk_words + row) * sizeof(uint32_t)));
-    TFHE_HIP(hipMemcpy(ck->d_ksk, ck->ksk_raw.data(), ksk_words * sizeof(uint32_t), hipMemcpyHostToDevice));
-    TFHE_HIP(hipMemset(ck->d_ksk + ksk_words, 0, row * sizeof(uint32_t)));
+    // key-switching key: rows padded to an even word count (8-byte aligned rows), plus one zero
+    // row (what digit 0 reads in the one-gate-per-workgroup kernel)
+    const size_t row = (size_t)P.n + 1, stride = (row + 1) & ~(size_t)1, rows = ksk_rows(P);
+    TFHE_HIP(hipMalloc((void **)&ck->d_ksk, (rows + 1) * stride * sizeof(uint32_t)));
+    TFHE_HIP(hipMemset(ck->d_ksk, 0, (rows + 1) * stride * sizeof(uint32_t)));
+    TFHE_HIP(hipMemcpy2D(ck->d_ksk, stride * sizeof(uint32_t), ck->ksk_raw.data(), row * sizeof(uint32_t),
+                         row * sizeof(uint32_t), rows, hipMemcpyHostToDevice));
 
     // bootstrapping key: raw to device, transform on device, raw copy released
     uint32_t *d_raw = nullptr;

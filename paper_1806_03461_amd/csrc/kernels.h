@@ -21,8 +21,9 @@ struct KeySwitchArgs {
     const tfhe_gate_rec *recs;   // device; NULL: gate i writes out[i]
     uint32_t *out;               // device wire array
     size_t count;
-    const uint32_t *ksk;         // device [1024][t][2^basebit - 1][n+1] plus one zero row
+    const uint32_t *ksk;         // device [1024][t][2^basebit - 1][stride] plus one zero row
     int n, t, basebit;
+    int stride;                  // words per key row on the device: n+1 rounded up to even, pad = 0
 };
 
 size_t blind_rotate_lds_bytes(int gates_per_group);

@@ -93,7 +93,8 @@ __global__ __launch_bounds__(64) void bk_to_spectrum_kernel(const uint32_t *__re
             const int32_t hi = (int16_t)(((w - (uint32_t)lo) >> 16) & 0xFFFFu);
             v[h] = limb ? hi : lo;
         }
-        x[m] = cmul(make_double2((double)v[0], (double)v[1]), ln.twist[m]);
+        // the 1/512 of the inverse transform is folded into the key (exact: a power of two)
+        x[m] = cmul(make_double2((double)v[0] * (1.0 / 512.0), (double)v[1] * (1.0 / 512.0)), ln.twist[m]);
     }
     forward_to_slots(x, ln, buf, L);
     wave_sync();
@@ -127,8 +128,8 @@ __device__ __forceinline__ void gate_constants(int op, uint32_t &kappa, uint32_t
     }
 }
 
-template <int B>
-__global__ __launch_bounds__(kThreadsPerGate *B) void blind_rotate_kernel(BlindRotateArgs a) {
+template <int B, bool MARGIN>
+__global__ __launch_bounds__(kThreadsPerGate *B) __attribute__((amdgpu_waves_per_eu(3, 3))) void blind_rotate_kernel(BlindRotateArgs a) {
     extern __shared__ __align__(16) unsigned char lds_raw[];
     GateLds *lds = reinterpret_cast<GateLds *>(lds_raw);
 
@@ -180,17 +181,20 @@ __global__ __launch_bounds__(kThreadsPerGate *B) void blind_rotate_kernel(BlindR
 
     const int comp = wv >> 1;                   // forward: component of D; inverse: component of ACC
     const int sel = wv & 1;                     // forward: digit index; inverse: limb
-    const int dshift = 32 - a.bgbit * (sel + 1);
-    const uint32_t dmask = (1u << a.bgbit) - 1u;
-    const int dhalf = 1 << (a.bgbit - 1);
-    const uint32_t doffset = ((uint32_t)dhalf << (32 - a.bgbit)) + ((uint32_t)dhalf << (32 - 2 * a.bgbit)) +
-                             (1u << (31 - 2 * a.bgbit));
+    // Signed digit `sel` of x: add the rounding constant and the half-bases of the lower digits
+    // (not its own: its two's-complement field then already is the centred digit), move the
+    // field to the top of the word, shift back down arithmetically.
+    const uint32_t dround = 1u << (31 - 2 * a.bgbit);
+    const uint32_t doffset = sel ? dround : dround + (1u << (31 - a.bgbit));
+    const int dlsh = sel ? a.bgbit : 0;
+    const int drsh = 32 - a.bgbit;
     double worst = 0.0;
 
     for (int i = 0; i < a.n; ++i) {
         // ---- rotate, subtract, decompose, fold and twist ----
         const int abar = my.bar[i];
-        const uint32_t *acc = my.acc[comp];
+        const unsigned char *accb = reinterpret_cast<const unsigned char *>(my.acc[comp]);
+        const uint32_t base = (uint32_t)(L - abar) << 2;       // byte offset of X^abar's source, mod 8192
         double2 x[8];
 #pragma unroll
         for (int m = 0; m < 8; ++m) {
@@ -198,10 +202,11 @@ __global__ __launch_bounds__(kThreadsPerGate *B) void blind_rotate_kernel(BlindR
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
                 const int j = L + 64 * m + h * kHalf;
-                const int src = (j - abar) & (2 * kN - 1);
-                const uint32_t p = acc[src & (kN - 1)];
-                const uint32_t d = (src < kN ? p : 0u - p) - acc[j];
-                dig[h] = (int32_t)(((d + doffset) >> dshift) & dmask) - dhalf;
+                const uint32_t src = (base + (uint32_t)(64 * m + h * kHalf) * 4u) & 8191u;
+                const uint32_t p = *reinterpret_cast<const uint32_t *>(accb + (src & 4095u));
+                const uint32_t neg = (uint32_t)((int32_t)(src << 19) >> 31);   // all ones past X^N
+                const uint32_t d = (p ^ neg) - (my.acc[comp][j] + neg);        // +-p - acc[j]
+                dig[h] = (int32_t)((d + doffset) << dlsh) >> drsh;
             }
             x[m] = cmul(make_double2((double)dig[0], (double)dig[1]), ln.twist[m]);
         }
@@ -212,27 +217,31 @@ __global__ __launch_bounds__(kThreadsPerGate *B) void blind_rotate_kernel(BlindR
         {
             const double2 *key = a.bk_fft + (size_t)i * 16 * kHalf;
             for (int s = tid; s < kHalf; s += kThreadsPerGate * B) {
-                double2 k[4][4];
+                double2 d[B][4];
 #pragma unroll
-                for (int r = 0; r < 4; ++r)
+                for (int q = 0; q < B; ++q)
 #pragma unroll
-                    for (int o = 0; o < 4; ++o) k[r][o] = key[(r * 4 + o) * kHalf + s];
+                    for (int r = 0; r < 4; ++r) d[q][r] = lds[q].spec[r][s];
+                // two outputs at a time keeps the key values of one pass in 32 registers
 #pragma unroll
-                for (int q = 0; q < B; ++q) {
-                    double2 d[4], y[4];
+                for (int half = 0; half < 2; ++half) {
+                    double2 k[4][2];
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) d[r] = lds[q].spec[r][s];
+                    for (int r = 0; r < 4; ++r)
 #pragma unroll
-                    for (int o = 0; o < 4; ++o) {
-                        y[o] = cmul(d[0], k[0][o]);
+                        for (int o = 0; o < 2; ++o) k[r][o] = key[(r * 4 + 2 * half + o) * kHalf + s];
 #pragma unroll
-                        for (int r = 1; r < 4; ++r) {
-                            y[o].x += d[r].x * k[r][o].x - d[r].y * k[r][o].y;
-                            y[o].y += d[r].x * k[r][o].y + d[r].y * k[r][o].x;
+                    for (int q = 0; q < B; ++q)
+#pragma unroll
+                        for (int o = 0; o < 2; ++o) {
+                            double2 y = cmul(d[q][0], k[0][o]);
+#pragma unroll
+                            for (int r = 1; r < 4; ++r) {
+                                y.x += d[q][r].x * k[r][o].x - d[q][r].y * k[r][o].y;
+                                y.y += d[q][r].x * k[r][o].y + d[q][r].y * k[r][o].x;
+                            }
+                            lds[q].spec[2 * half + o][s] = y;
                         }
-                    }
-#pragma unroll
-                    for (int o = 0; o < 4; ++o) lds[q].spec[o][s] = y[o];
                 }
             }
         }
@@ -243,13 +252,13 @@ __global__ __launch_bounds__(kThreadsPerGate *B) void blind_rotate_kernel(BlindR
 #pragma unroll
         for (int m = 0; m < 8; ++m) {
             const double2 v = cmulc(x[m], ln.twist[m]);
-            const double part[2] = {v.x * (1.0 / 512.0), v.y * (1.0 / 512.0)};
+            const double part[2] = {v.x, v.y};
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
                 // adding 1.5 * 2^52 leaves round-to-nearest(part) mod 2^32 in the low word
                 const double shifted = part[h] + 6755399441055744.0;
                 uint32_t r = (uint32_t)__double2loint(shifted);
-                if (a.margin) worst = fmax(worst, fabs(part[h] - (shifted - 6755399441055744.0)));
+                if (MARGIN) worst = fmax(worst, fabs(part[h] - (shifted - 6755399441055744.0)));
                 if (sel) r <<= 16;
                 atomicAdd(&my.acc[comp][L + 64 * m + h * kHalf], r);
             }
@@ -263,7 +272,7 @@ __global__ __launch_bounds__(kThreadsPerGate *B) void blind_rotate_kernel(BlindR
         for (int j = lt; j < kN; j += kThreadsPerGate) ext[j] = j == 0 ? my.acc[0][0] : 0u - my.acc[0][kN - j];
         if (lt == 0) ext[kN] = my.acc[1][0];
     }
-    if (a.margin) {
+    if (MARGIN) {
         // non-negative doubles order like their bit patterns
         atomicMax(reinterpret_cast<unsigned long long *>(a.margin),
                   (unsigned long long)__double_as_longlong(worst));
@@ -294,7 +303,7 @@ __global__ __launch_bounds__(256) void key_switch_kernel(KeySwitchArgs a) {
     }
     const int values = (1 << a.basebit) - 1;
     const uint32_t round = 1u << (31 - T * a.basebit);
-    const size_t zero_row = (size_t)kN * T * values;
+    const size_t zero_row = (size_t)kN * T * values;   // appended row of zeros
     const int per_thread = (words + 255) >> 8;
     for (int i = 0; i < kN; ++i) {
         const uint32_t ai = ext[i] + round;
@@ -303,7 +312,7 @@ __global__ __launch_bounds__(256) void key_switch_kernel(KeySwitchArgs a) {
         for (int j = 0; j < T; ++j) {
             const uint32_t v = (ai >> (32 - a.basebit * (j + 1))) & (uint32_t)values;
             const size_t row = v ? ((size_t)i * T + j) * values + (v - 1) : zero_row;
-            rows[j] = a.ksk + row * (size_t)words;
+            rows[j] = a.ksk + row * (size_t)a.stride;
         }
         for (int q = 0; q < per_thread; ++q) {
             const int w = tid + 256 * q;
@@ -324,6 +333,87 @@ __global__ __launch_bounds__(256) void key_switch_kernel(KeySwitchArgs a) {
     for (int q = 0; q < kMaxPerThread; ++q) {
         const int w = tid + 256 * q;
         if (w < words) out[w] = acc[q];
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Key switch, G gates per workgroup (the fast path for t = 8 digits in base 4, n + 1 <= 512).
+// Every key row is loaded once per workgroup and subtracted from the gates whose digit selects
+// it, so the key traffic per gate is 1/G of the one-gate-per-workgroup kernel.  Thread p owns the
+// adjacent output words 2p, 2p+1 of all G gates.  For one (mask word i, digit position j) each
+// wave parks its 128-word slice of the three rows in a private LDS table whose row 0 stays
+// zero; a gate's digit is uniform over the workgroup, so the gate picks its row with a uniform
+// LDS offset -- the LDS does the gather.  The rounded mask words of the G gates are staged
+// through LDS 64 at a time.
+// ------------------------------------------------------------------------------------------
+template <int G>
+__global__ __launch_bounds__(256) void key_switch_shared_kernel(KeySwitchArgs a) {
+    constexpr int T = 8, kChunk = 64;
+    __shared__ uint32_t mask_words[kChunk][G];
+    __shared__ uint2 stage[4][4][64];             // [wave][digit value][lane]
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6, lane = tid & 63;
+    const size_t g0 = (size_t)blockIdx.x * G;
+    const int words = a.n + 1;
+    const bool owner = 2 * tid < words;            // 2p+1 may be the zero padding word of a row
+    const int pair = owner ? tid : 0;              // idle threads shadow pair 0 and store nothing
+
+    uint2 acc[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        const bool live = g0 + g < a.count;
+        const uint32_t body = live ? a.ext[(g0 + g) * (size_t)(kN + 1) + kN] : 0u;
+        acc[g].x = 2 * pair == a.n ? body : 0u;
+        acc[g].y = 2 * pair + 1 == a.n ? body : 0u;
+    }
+    stage[wave][0][lane] = make_uint2(0u, 0u);
+    const uint32_t round = 1u << (31 - T * 2);
+    const unsigned char *table = reinterpret_cast<const unsigned char *>(&stage[wave][0][lane]);
+    for (int i0 = 0; i0 < kN; i0 += kChunk) {
+        __syncthreads();
+        for (int idx = tid; idx < kChunk * G; idx += 256) {
+            const int g = idx / kChunk, ii = idx % kChunk;
+            const bool live = g0 + g < a.count;
+            mask_words[ii][g] = live ? a.ext[(g0 + g) * (size_t)(kN + 1) + i0 + ii] + round : 0u;
+        }
+        __syncthreads();
+        for (int ii = 0; ii < kChunk; ++ii) {
+            const uint32_t *rows = a.ksk + (size_t)(i0 + ii) * T * 3 * a.stride;
+            uint2 r[T][3];
+#pragma unroll
+            for (int j = 0; j < T; ++j)
+#pragma unroll
+                for (int v = 0; v < 3; ++v)
+                    r[j][v] = *reinterpret_cast<const uint2 *>(rows + (size_t)(j * 3 + v) * a.stride + 2 * pair);
+            uint32_t ai[G];
+#pragma unroll
+            for (int g = 0; g < G; ++g) ai[g] = __builtin_amdgcn_readfirstlane(mask_words[ii][g]);
+#pragma unroll
+            for (int j = 0; j < T; ++j) {
+                wave_sync();                       // the previous table has been read by every lane
+#pragma unroll
+                for (int v = 0; v < 3; ++v) stage[wave][v + 1][lane] = r[j][v];
+                wave_sync();
+#pragma unroll
+                for (int g = 0; g < G; ++g) {
+                    const uint32_t v = (ai[g] >> (30 - 2 * j)) & 3u;
+                    const uint2 sub = *reinterpret_cast<const uint2 *>(table + v * (64 * sizeof(uint2)));
+                    acc[g].x -= sub.x;
+                    acc[g].y -= sub.y;
+                }
+            }
+        }
+    }
+    if (owner) {
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            if (g0 + g < a.count) {
+                const size_t out_index = a.recs ? (size_t)a.recs[g0 + g].out : g0 + g;
+                uint32_t *out = a.out + out_index * (size_t)words;
+                out[2 * pair] = acc[g].x;
+                if (2 * pair + 1 < words) out[2 * pair + 1] = acc[g].y;
+            }
+        }
     }
 }
 
@@ -366,12 +456,17 @@ static int launch_br(const BlindRotateArgs &a, hipStream_t stream) {
     const size_t lds = blind_rotate_lds_bytes(B);
     static bool configured = false;
     if (!configured) {
-        TFHE_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&blind_rotate_kernel<B>),
+        TFHE_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&blind_rotate_kernel<B, false>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        TFHE_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&blind_rotate_kernel<B, true>),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         configured = true;
     }
     const unsigned blocks = (unsigned)((a.count + B - 1) / B);
-    hipLaunchKernelGGL(blind_rotate_kernel<B>, dim3(blocks), dim3(kThreadsPerGate * B), lds, stream, a);
+    if (a.margin)
+        hipLaunchKernelGGL((blind_rotate_kernel<B, true>), dim3(blocks), dim3(kThreadsPerGate * B), lds, stream, a);
+    else
+        hipLaunchKernelGGL((blind_rotate_kernel<B, false>), dim3(blocks), dim3(kThreadsPerGate * B), lds, stream, a);
     TFHE_HIP(hipGetLastError());
     return TFHE_OK;
 }
@@ -388,6 +483,13 @@ int launch_blind_rotate(const BlindRotateArgs &a, int gates_per_group, hipStream
 
 int launch_key_switch(const KeySwitchArgs &a, hipStream_t stream) {
     if (a.count == 0) return TFHE_OK;
+    if (a.t == 8 && a.basebit == 2 && a.n + 1 <= 512) {
+        constexpr int G = 16;
+        hipLaunchKernelGGL(key_switch_shared_kernel<G>, dim3((unsigned)((a.count + G - 1) / G)), dim3(256), 0,
+                           stream, a);
+        TFHE_HIP(hipGetLastError());
+        return TFHE_OK;
+    }
     const dim3 grid((unsigned)a.count), block(256);
     switch (a.t) {
 #define KS_CASE(T) case T: hipLaunchKernelGGL(key_switch_kernel<T>, grid, block, 0, stream, a); break;

@@ -1,0 +1,194 @@
+"""GPU parity on the five benchmark configurations at full size, in the launch configuration
+the benchmark times.
+
+Three kinds of evidence, strongest first:
+  1. sampled whole units (neurons / pixels) against tests/golden/sampled_outputs.json, which the
+     CPU oracle computed from scratch from the seeded inputs (bit-exact ciphertext digests);
+  2. every output of every configuration decrypted and compared with the exact integer layer;
+  3. a local property that holds at any size: randomly sampled gates deep inside the circuit,
+     re-evaluated by the oracle on the GPU's own input wires, give the GPU's output wire bytes.
+"""
+import hashlib
+import json
+import os
+
+import numpy as np
+import pytest
+
+import workloads
+from oracle import circuits as cc
+
+pytestmark = pytest.mark.gpu
+GOLD = os.path.join(os.path.dirname(__file__), "golden", "sampled_outputs.json")
+
+
+def digest(ct):
+    return hashlib.sha256(np.ascontiguousarray(ct, dtype="<u4").tobytes()).hexdigest()
+
+
+@pytest.fixture(scope="module")
+def golden():
+    g = json.load(open(GOLD))
+    assert g["key_seed"] == workloads.KEY_SEED
+    table = {}
+    for e in g["entries"]:
+        table[(e["cfg"], tuple(e["unit"]))] = e
+    return table
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    import paper_1806_03461_amd as T
+    sk, ck = T.tfhe_keygen(T.default_params(), workloads.KEY_SEED)
+    T.tfhe_cloud_key_upload(ck)
+    return T, sk, ck
+
+
+def test_cfg2_one_neuron_bit_exact(gpu, golden):
+    import torch
+    T, sk, ck = gpu
+    c = workloads.cfg2()
+    x = T.to_device(T.tfhe_encrypt(sk, c["enc_seed"], c["x"]))
+    out = torch.empty((1, 501), dtype=torch.int32, device="cuda")
+    for Tt in (int(c["T"][0]), 128):
+        T.bnn_dense_encrypted(ck, x, 256, c["W"], np.array([Tt], np.int32), 1, out)
+        torch.cuda.synchronize()
+        got = T.to_host(out)[0]
+        e = golden[("cfg2", (Tt,))]
+        assert digest(got) == e["sha256"]
+        assert T.tfhe_decrypt(sk, got)[0] == e["bit"] == cc.dense_plain(c["x"], c["W"], np.array([Tt]))[0]
+
+
+def test_cfg3_dense_layer(gpu, golden, real_keys):
+    import torch
+    T, sk, ck = gpu
+    c = workloads.cfg3()
+    ctx = T.tfhe_encrypt(sk, c["enc_seed"], c["x"])
+    gates, outs, nw = T.bnn_dense_lower(784, c["W"], c["T"], 512)
+    wires = torch.zeros((nw, 501), dtype=torch.int32, device="cuda")
+    wires[:784] = T.to_device(ctx)
+    wires[784] = T.to_device(T.tfhe_trivial(T.default_params(), 0).reshape(1, -1))[0]
+    wires[785] = T.to_device(T.tfhe_trivial(T.default_params(), 1).reshape(1, -1))[0]
+    T.tfhe_gate_stream(ck, gates, wires, nw)
+    torch.cuda.synchronize()
+    assert (outs["wire"] >= 0).all()
+    idx = torch.from_numpy(outs["wire"].astype(np.int64)).cuda()
+    out = T.to_host(wires[idx])
+    neg = outs["value"].astype(bool)
+    out[neg] = (0 - out[neg]).astype(np.uint32)
+    # (2) all 512 outputs against the integer layer
+    assert np.array_equal(T.tfhe_decrypt(sk, out), cc.dense_plain(c["x"], c["W"], c["T"]))
+    # (1) whole neurons computed from scratch by the oracle
+    for j in (0, 257):
+        assert digest(out[j]) == golden[("cfg3", (j,))]["sha256"], j
+    # (3) 256 random gates anywhere in the circuit, oracle on the GPU's input wires
+    rng = np.random.default_rng(33)
+    pick = np.sort(rng.choice(len(gates), 256, replace=False))
+    sel = gates[pick]
+    take = lambda w: T.to_host(wires[torch.from_numpy(w.astype(np.int64)).cuda()])
+    k = len(sel)
+    work = np.concatenate([take(sel["in0"]), take(sel["in1"]), np.zeros((k, 501), np.uint32)])
+    recs = sel.copy()
+    recs["in0"], recs["in1"], recs["out"] = np.arange(k), k + np.arange(k), 2 * k + np.arange(k)
+    real_keys.gate_batch(recs, work, threads=16)
+    assert np.array_equal(work[2 * k:], take(sel["out"]))
+
+
+def test_cfg4_conv_layer(gpu, golden):
+    import torch
+    T, sk, ck = gpu
+    c = workloads.cfg4()
+    x = T.to_device(T.tfhe_encrypt(sk, c["enc_seed"], c["x"].reshape(-1)))
+    out = torch.empty((32 * 28 * 28, 501), dtype=torch.int32, device="cuda")
+    T.bnn_conv_encrypted(ck, x, 16, 28, 28, c["K"], c["T"], 1, 1, out)
+    torch.cuda.synchronize()
+    got = T.to_host(out)
+    plain = cc.conv_plain(c["x"], c["K"], c["T"], 1, 1)
+    assert np.array_equal(T.tfhe_decrypt(sk, got).reshape(32, 28, 28), plain)
+    for (o, y, xx) in [(0, 0, 0), (5, 0, 13), (17, 13, 27), (31, 27, 27), (9, 14, 14), (20, 27, 3)]:
+        assert digest(got[(o * 28 + y) * 28 + xx]) == golden[("cfg4", (o, y, xx))]["sha256"], (o, y, xx)
+
+
+def test_cfg5_sparse_mlp(gpu, golden, real_keys):
+    import torch
+    T, sk, ck = gpu
+    c = workloads.cfg5()
+    h = T.to_device(T.tfhe_encrypt(sk, c["enc_seed"], c["x"]))
+    acts = [h]
+    plain = [c["x"]]
+    for li, layer in enumerate(c["layers"]):
+        p, d = layer["W"].shape
+        last = layer["T"] is None
+        out = torch.empty((p * (c["out_bits"] if last else 1), 501), dtype=torch.int32, device="cuda")
+        T.bnn_dense_encrypted(ck, acts[-1], d, layer["W"], layer["T"], p, out, c["out_bits"] if last else 0)
+        acts.append(out)
+        plain.append(cc.dense_plain(plain[-1], layer["W"], layer["T"]))
+    torch.cuda.synchronize()
+    host = [T.to_host(a) for a in acts]
+    # (2) every activation of every layer against the plain integer network
+    for li in (1, 2):
+        assert np.array_equal(T.tfhe_decrypt(sk, host[li]), plain[li]), li
+    bits = T.tfhe_decrypt(sk, host[3]).reshape(10, c["out_bits"]).astype(np.int64)
+    assert np.array_equal((bits << np.arange(c["out_bits"])).sum(axis=1), plain[3])
+    # (1) first-layer neurons from scratch
+    for j in (0, 100):
+        assert digest(host[1][j]) == golden[("cfg5", (0, j))]["sha256"], j
+    # (3) one whole neuron of each later layer, oracle fed with the GPU's activations
+    for li, j in ((1, 7), (2, 3)):
+        layer = c["layers"][li]
+        last = layer["T"] is None
+        cir, outs = cc.dense_layer(layer["W"].shape[1], layer["W"][j:j + 1],
+                                   None if last else layer["T"][j:j + 1], c["out_bits"])
+        ref, _ = cc.eval_encrypted(real_keys, cir, host[li], outs, threads=16)
+        mine = host[li + 1][j * c["out_bits"]:(j + 1) * c["out_bits"]] if last else host[li + 1][j:j + 1]
+        assert np.array_equal(mine, ref), (li, j)
+
+
+def test_degenerate_units(gpu, real_keys):
+    """Constant outputs (T <= 0, T > m, all-zero row), a single negated input passed through
+    without any gate, and a layer with no gates at all."""
+    import torch
+    T, sk, ck = gpu
+    x = np.array([1, 0, 1, 1, 0], np.uint8)
+    ctx = T.tfhe_encrypt(sk, 61, x)
+    W = np.array([[0, 0, 0, 0, 0], [0, -1, 0, 0, 0], [1, 1, 1, 1, 1], [1, -1, 1, 1, -1], [0, 0, 1, 0, 0]], np.int8)
+    Tt = np.array([0, 1, 6, -3, 1], np.int32)
+    out = torch.empty((5, 501), dtype=torch.int32, device="cuda")
+    T.bnn_dense_encrypted(ck, T.to_device(ctx), 5, W, Tt, 5, out)
+    torch.cuda.synchronize()
+    got = T.to_host(out)
+    cir, o = cc.dense_layer(5, W, Tt)
+    ref, _ = cc.eval_encrypted(real_keys, cir, ctx, o, threads=4)
+    assert len(cir.gates) == 0
+    assert np.array_equal(got, ref)
+    assert np.array_equal(got[1], (0 - ctx[1]).astype(np.uint32)) and np.array_equal(got[4], ctx[2])
+    assert list(T.tfhe_decrypt(sk, got)) == [1, 1, 0, 1, 1] == list(cc.dense_plain(x, W, Tt))
+
+
+def test_small_convolution_entry_point(gpu, real_keys):
+    """Stride 2 and stride 1 on a 2x6x5 image: every pixel's ciphertext against the oracle's own
+    lowering (3 + 12 pixels of 18 taps each)."""
+    import torch
+    T, sk, ck = gpu
+    rng = np.random.default_rng(71)
+    x = rng.integers(0, 2, (2, 6, 5)).astype(np.uint8)
+    K = (2 * rng.integers(0, 2, (2, 2, 3, 3)) - 1).astype(np.int8)
+    K[0, 1, 1, 1] = 0
+    Tt = np.array([8, 10], np.int32)
+    ctx = T.tfhe_encrypt(sk, 72, x.reshape(-1))
+    for stride, pad, pixels in ((2, 0, None), (1, 1, [(0, 0, 0), (1, 5, 4), (0, 2, 2), (1, 0, 3)])):
+        Ho, Wo = (6 + 2 * pad - 3) // stride + 1, (5 + 2 * pad - 3) // stride + 1
+        out = torch.empty((2 * Ho * Wo, 501), dtype=torch.int32, device="cuda")
+        T.bnn_conv_encrypted(ck, T.to_device(ctx), 2, 6, 5, K, Tt, stride, pad, out)
+        torch.cuda.synchronize()
+        got = T.to_host(out)
+        assert np.array_equal(T.tfhe_decrypt(sk, got).reshape(2, Ho, Wo), cc.conv_plain(x, K, Tt, stride, pad))
+        cir, o = cc.conv_layer(2, 6, 5, K, Tt, stride, pad, pixels=pixels)
+        ref, _ = cc.eval_encrypted(real_keys, cir, ctx, o, threads=16)
+        if pixels is None:
+            assert np.array_equal(got, ref)
+        else:
+            for k, (oc, y, xx) in enumerate(pixels):
+                assert np.array_equal(got[(oc * Ho + y) * Wo + xx], ref[k])
