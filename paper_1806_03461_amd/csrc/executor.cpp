@@ -51,6 +51,20 @@ int gates_per_group() {
     return cached;
 }
 
+// Gates per key-switch workgroup: large batches amortise the 49 MB key over 16 gates; small
+// batches (the deep, narrow levels of a circuit) need many short workgroups instead.
+int key_switch_group(size_t count) {
+    static int forced = -1;
+    if (forced < 0) {
+        const char *e = getenv("TFHE_KS_GROUP");
+        forced = e ? atoi(e) : 0;
+    }
+    if (forced > 0) return forced;
+    if (count >= 8192) return 16;
+    if (count >= 2048) return 4;
+    return 1;
+}
+
 int check_cloud_key(const tfhe_cloud_key *ck) {
     if (!ck) return set_error(TFHE_E_NULL, "cloud key is NULL");
     if (ck->magic != TFHE_CK_MAGIC) return set_error(TFHE_E_PARAM, "not a cloud key");
@@ -84,6 +98,7 @@ int run_batch(tfhe_cloud_key *ck, const tfhe_gate_rec *d_recs, int uniform_op, c
     KeySwitchArgs ks{};
     ks.ext = br.ext; ks.recs = d_recs; ks.out = out; ks.count = count; ks.ksk = ck->d_ksk;
     ks.n = P.n; ks.t = P.ks_t; ks.basebit = P.ks_basebit; ks.stride = (P.n + 2) & ~1;
+    ks.group = key_switch_group(count);
 
     TimedLaunch tl{};
     if (ck->profile) if (int rc = begin_timed(ck, 0, stream, tl)) return rc;
@@ -175,13 +190,11 @@ int tfhe_cloud_key_upload(tfhe_cloud_key *ck) {
     if (count < 1) return set_error(TFHE_E_HIP, "no HIP device");
     TFHE_HIP(hipGetDevice(&ck->device));
 
-    // twiddle tables: w512^k and psi^j, evaluated in extended precision
-    std::vector<double2> tables(1024);
+    // twiddle table psi^j = exp(i pi j / 1024), j < 2048, evaluated in extended precision
+    std::vector<double2> tables(2048);
     const long double pi = 3.14159265358979323846264338327950288L;
-    for (int k = 0; k < 512; ++k) {
-        tables[k] = make_double2((double)cosl(2 * pi * k / 512), (double)sinl(2 * pi * k / 512));
-        tables[512 + k] = make_double2((double)cosl(pi * k / 1024), (double)sinl(pi * k / 1024));
-    }
+    for (int j = 0; j < 2048; ++j)
+        tables[j] = make_double2((double)cosl(pi * j / 1024), (double)sinl(pi * j / 1024));
     TFHE_HIP(hipMalloc((void **)&ck->d_tables, tables.size() * sizeof(double2)));
     TFHE_HIP(hipMemcpy(ck->d_tables, tables.data(), tables.size() * sizeof(double2), hipMemcpyHostToDevice));
 

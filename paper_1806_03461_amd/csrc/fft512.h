@@ -2,14 +2,14 @@
 // polynomials of Z[X]/(X^1024+1) exactly.
 //
 // A real polynomial a of degree < N = 1024 is folded to z_j = (a_j + i a_{j+512}) psi^j,
-// psi = exp(i pi / N); its 512-point DFT (kernel exp(+2 pi i jk/512)) holds the values of a
+// psi = exp(i pi / N) (the twist is applied inside pass 1); its 512-point DFT (kernel exp(+2 pi i jk/512)) holds the values of a
 // at the roots psi^(4k+1) of X^N + 1 -- half of the roots, the others being the conjugates.
 // Products of such values are the values of the product polynomial mod X^N + 1, and the
 // inverse transform followed by the multiplication with psi^-j gives its coefficients back
 // in the real and imaginary parts.
 //
 // The transform is radix 8 x 8 x 8.  Forward (decimation in frequency):
-//   pass 1  lane L holds z[L + 64 m], m = 0..7; DFT over m, times w512^(L k0)
+//   pass 1  lane L holds point L + 64 m, m = 0..7; twist, DFT over m, times w512^(L k0)
 //   T1      through LDS: lane (k0, j0) receives the eight j1 values of row k0
 //   pass 2  DFT over j1, times w64^(j0 k1)
 //   T2      through LDS within groups of 8 lanes: lane (k0, k1) receives the eight j0 values
@@ -75,27 +75,38 @@ FFT_HD void radix8(double2 (&x)[8]) {
     }
 }
 
+// psi^(64 m) = exp(i pi m / 16), m = 0..7: the part of the negacyclic twist psi^(L + 64 m) that
+// does not depend on the lane.  It is applied to the inputs of pass 1; the lane's own psi^L is
+// merged into the pass-1 twiddles.
+FFT_HD double2 twist_const(int m) {
+    const double c[8] = {1.0, 0.98078528040323044913, 0.92387953251128675613, 0.83146961230254523708,
+                         0.70710678118654752440, 0.55557023301960222474, 0.38268343236508977173,
+                         0.19509032201612826785};
+    const double s[8] = {0.0, 0.19509032201612826785, 0.38268343236508977173, 0.55557023301960222474,
+                         0.70710678118654752440, 0.83146961230254523708, 0.92387953251128675613,
+                         0.98078528040323044913};
+    return make_double2(c[m], s[m]);
+}
+
 // Per-lane constants, loaded once per kernel and kept in registers.
 struct Lane {
-    double2 tw1[8];    // w512^(L k)
-    double2 tw2[8];    // w64^((L & 7) k)
-    double2 twist[8];  // psi^(L + 64 m)
+    double2 tw1[8];    // psi^L * w512^(L k) = psi^(L (1 + 4k))
+    double2 tw2[8];    // w64^((L & 7) k)    = psi^(32 (L & 7) k)
 };
 
-// tables: [0, 512) = w512^k, [512, 1024) = psi^j
+// tables[j] = psi^j = exp(i pi j / 1024), j < 2048
 FFT_HD void lane_init(Lane &ln, const double2 *tables, int L) {
     for (int k = 0; k < 8; ++k) {
-        ln.tw1[k] = tables[(L * k) & 511];
-        ln.tw2[k] = tables[((L & 7) * k * 8) & 511];
-        ln.twist[k] = tables[512 + L + 64 * k];
+        ln.tw1[k] = tables[L * (1 + 4 * k)];
+        ln.tw2[k] = tables[32 * (L & 7) * k];
     }
 }
 
-// ---- forward -------------------------------------------------------------------
+// ---- forward: x[m] holds the folded, untwisted point a[L + 64 m] + i a[L + 64 m + 512] -------
 FFT_HD void fwd_pass1_store(double2 (&x)[8], const Lane &ln, double2 *buf, int L) {
+    for (int m = 1; m < 8; ++m) x[m] = cmul(x[m], twist_const(m));
     radix8<false>(x);
-    buf[L] = x[0];
-    for (int k = 1; k < 8; ++k) buf[k * kRowStride + L] = cmul(x[k], ln.tw1[k]);
+    for (int k = 0; k < 8; ++k) buf[k * kRowStride + L] = cmul(x[k], ln.tw1[k]);
 }
 FFT_HD void fwd_pass2_load(double2 (&x)[8], const double2 *buf, int L) {
     const int row = (L >> 3) * kRowStride, j0 = L & 7;
@@ -113,7 +124,7 @@ FFT_HD void fwd_pass3(double2 (&x)[8], const double2 *buf, int L) {
     radix8<false>(x);
 }
 
-// ---- inverse (unnormalised: the caller scales by 1/512) ---------------------------
+// ---- inverse (unnormalised: 512 times the folded, untwisted points come out) -----------
 FFT_HD void inv_pass3_store(double2 (&x)[8], const Lane &ln, double2 *buf, int L) {
     radix8<true>(x);
     const int base = (L >> 3) * kRowStride + (L & 7) * kGrpStride;
@@ -130,9 +141,9 @@ FFT_HD void inv_pass2_store(const double2 (&x)[8], double2 *buf, int L) {
     for (int j1 = 0; j1 < 8; ++j1) buf[row + j0 + 8 * j1] = x[j1];
 }
 FFT_HD void inv_pass1(double2 (&x)[8], const Lane &ln, const double2 *buf, int L) {
-    x[0] = buf[L];
-    for (int k = 1; k < 8; ++k) x[k] = cmulc(buf[k * kRowStride + L], ln.tw1[k]);
+    for (int k = 0; k < 8; ++k) x[k] = cmulc(buf[k * kRowStride + L], ln.tw1[k]);
     radix8<true>(x);
+    for (int m = 1; m < 8; ++m) x[m] = cmulc(x[m], twist_const(m));
 }
 
 }  // namespace fft512

@@ -11,7 +11,7 @@ struct BlindRotateArgs {
     uint32_t *ext;               // device [count][1025]: extracted samples
     size_t count;
     const double2 *bk_fft;       // device [n][4][4][512]
-    const double2 *tables;       // device [1024]
+    const double2 *tables;       // device [2048]: exp(i pi j / 1024)
     int n, bgbit;
     double *margin;              // device, optional: largest rounding distance seen
 };
@@ -23,6 +23,7 @@ struct KeySwitchArgs {
     size_t count;
     const uint32_t *ksk;         // device [1024][t][2^basebit - 1][stride] plus one zero row
     int n, t, basebit;
+    int group;                   // gates sharing one pass over the key (1 = one gate per workgroup)
     int stride;                  // words per key row on the device: n+1 rounded up to even, pad = 0
 };
 

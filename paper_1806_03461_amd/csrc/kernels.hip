@@ -35,7 +35,7 @@ __device__ __forceinline__ void wave_sync() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-// Forward transform of the 8 folded, twisted points held in x; leaves the spectrum in buf in
+// Forward transform of the 8 folded points held in x; leaves the spectrum in buf in
 // slot order (slot = 64 * register + lane).
 __device__ __forceinline__ void forward_to_slots(double2 (&x)[8], const Lane &ln, double2 *buf, int L) {
     fwd_pass1_store(x, ln, buf, L);
@@ -50,8 +50,8 @@ __device__ __forceinline__ void forward_to_slots(double2 (&x)[8], const Lane &ln
     for (int k = 0; k < 8; ++k) buf[k * 64 + L] = x[k];
 }
 
-// Inverse transform of the spectrum held in buf (slot order); x[m] is 512 times the folded,
-// still twisted point L + 64 m.
+// Inverse transform of the spectrum held in buf (slot order); x[m] is 512 times the folded
+// point L + 64 m (real part: coefficient L + 64 m, imaginary part: coefficient L + 64 m + 512).
 __device__ __forceinline__ void inverse_from_slots(double2 (&x)[8], const Lane &ln, double2 *buf, int L) {
 #pragma unroll
     for (int k = 0; k < 8; ++k) x[k] = buf[k * 64 + L];
@@ -94,7 +94,7 @@ __global__ __launch_bounds__(64) void bk_to_spectrum_kernel(const uint32_t *__re
             v[h] = limb ? hi : lo;
         }
         // the 1/512 of the inverse transform is folded into the key (exact: a power of two)
-        x[m] = cmul(make_double2((double)v[0] * (1.0 / 512.0), (double)v[1] * (1.0 / 512.0)), ln.twist[m]);
+        x[m] = make_double2((double)v[0] * (1.0 / 512.0), (double)v[1] * (1.0 / 512.0));
     }
     forward_to_slots(x, ln, buf, L);
     wave_sync();
@@ -208,7 +208,7 @@ __global__ __launch_bounds__(kThreadsPerGate *B) __attribute__((amdgpu_waves_per
                 const uint32_t d = (p ^ neg) - (my.acc[comp][j] + neg);        // +-p - acc[j]
                 dig[h] = (int32_t)((d + doffset) << dlsh) >> drsh;
             }
-            x[m] = cmul(make_double2((double)dig[0], (double)dig[1]), ln.twist[m]);
+            x[m] = make_double2((double)dig[0], (double)dig[1]);
         }
         forward_to_slots(x, ln, my.spec[wv], L);
         __syncthreads();
@@ -251,8 +251,7 @@ __global__ __launch_bounds__(kThreadsPerGate *B) __attribute__((amdgpu_waves_per
         inverse_from_slots(x, ln, my.spec[wv], L);
 #pragma unroll
         for (int m = 0; m < 8; ++m) {
-            const double2 v = cmulc(x[m], ln.twist[m]);
-            const double part[2] = {v.x, v.y};
+            const double part[2] = {x[m].x, x[m].y};
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
                 // adding 1.5 * 2^52 leaves round-to-nearest(part) mod 2^32 in the low word
@@ -483,10 +482,15 @@ int launch_blind_rotate(const BlindRotateArgs &a, int gates_per_group, hipStream
 
 int launch_key_switch(const KeySwitchArgs &a, hipStream_t stream) {
     if (a.count == 0) return TFHE_OK;
-    if (a.t == 8 && a.basebit == 2 && a.n + 1 <= 512) {
-        constexpr int G = 16;
-        hipLaunchKernelGGL(key_switch_shared_kernel<G>, dim3((unsigned)((a.count + G - 1) / G)), dim3(256), 0,
-                           stream, a);
+    if (a.t == 8 && a.basebit == 2 && a.n + 1 <= 512 && a.group > 1) {
+        // more gates per workgroup = less key traffic per gate but fewer, longer workgroups
+#define KS_SHARED(G)                                                                                   \
+    hipLaunchKernelGGL(key_switch_shared_kernel<G>, dim3((unsigned)((a.count + G - 1) / G)), dim3(256), 0, \
+                       stream, a)
+        if (a.group >= 16) KS_SHARED(16);
+        else if (a.group >= 8) KS_SHARED(8);
+        else KS_SHARED(4);
+#undef KS_SHARED
         TFHE_HIP(hipGetLastError());
         return TFHE_OK;
     }
