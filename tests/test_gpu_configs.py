@@ -147,7 +147,7 @@ def test_cfg5_sparse_mlp(gpu, golden, real_keys):
 
 
 def test_degenerate_units(gpu, real_keys):
-    """Constant outputs (T <= 0, T > m, all-zero row), a single negated input passed through
+    """Constant outputs (T <= 0, T > m, all-zero row), a single (negated) input passed through
     without any gate, and a layer with no gates at all."""
     import torch
     T, sk, ck = gpu
@@ -155,16 +155,20 @@ def test_degenerate_units(gpu, real_keys):
     ctx = T.tfhe_encrypt(sk, 61, x)
     W = np.array([[0, 0, 0, 0, 0], [0, -1, 0, 0, 0], [1, 1, 1, 1, 1], [1, -1, 1, 1, -1], [0, 0, 1, 0, 0]], np.int8)
     Tt = np.array([0, 1, 6, -3, 1], np.int32)
-    out = torch.empty((5, 501), dtype=torch.int32, device="cuda")
-    T.bnn_dense_encrypted(ck, T.to_device(ctx), 5, W, Tt, 5, out)
-    torch.cuda.synchronize()
-    got = T.to_host(out)
-    cir, o = cc.dense_layer(5, W, Tt)
-    ref, _ = cc.eval_encrypted(real_keys, cir, ctx, o, threads=4)
-    assert len(cir.gates) == 0
-    assert np.array_equal(got, ref)
-    assert np.array_equal(got[1], (0 - ctx[1]).astype(np.uint32)) and np.array_equal(got[4], ctx[2])
-    assert list(T.tfhe_decrypt(sk, got)) == [1, 1, 0, 1, 1] == list(cc.dense_plain(x, W, Tt))
+    for rows in ([0, 1, 4], [0, 1, 2, 3, 4]):
+        p = len(rows)
+        out = torch.empty((p, 501), dtype=torch.int32, device="cuda")
+        T.bnn_dense_encrypted(ck, T.to_device(ctx), 5, W[rows], Tt[rows], p, out)
+        torch.cuda.synchronize()
+        got = T.to_host(out)
+        cir, o = cc.dense_layer(5, W[rows], Tt[rows])
+        ref, _ = cc.eval_encrypted(real_keys, cir, ctx, o, threads=4)
+        if p == 3:
+            assert len(cir.gates) == 0 and len(T.bnn_dense_lower(5, W[rows], Tt[rows], p)[0]) == 0
+        assert np.array_equal(got, ref)
+        assert np.array_equal(got[1], (0 - ctx[1]).astype(np.uint32)) and np.array_equal(got[-1], ctx[2])
+        assert list(T.tfhe_decrypt(sk, got)) == list(cc.dense_plain(x, W[rows], Tt[rows]))
+    assert list(cc.dense_plain(x, W, Tt)) == [1, 1, 0, 1, 1]
 
 
 def test_small_convolution_entry_point(gpu, real_keys):
