@@ -128,6 +128,16 @@ __device__ __forceinline__ void gate_constants(int op, uint32_t &kappa, uint32_t
     }
 }
 
+// 16-byte load from a buffer: descriptor and soffset are scalar, voffset is the lane's byte offset
+__device__ __forceinline__ double2 load_key(__amdgpu_buffer_rsrc_t rsrc, uint32_t voffset, uint32_t soffset) {
+    typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+    const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)voffset, (int)soffset, 0);
+    double2 out;
+    out.x = __hiloint2double((int)v.y, (int)v.x);
+    out.y = __hiloint2double((int)v.w, (int)v.z);
+    return out;
+}
+
 template <int B, bool MARGIN>
 __global__ __launch_bounds__(kThreadsPerGate *B) __attribute__((amdgpu_waves_per_eu(3, 3))) void blind_rotate_kernel(BlindRotateArgs a) {
     extern __shared__ __align__(16) unsigned char lds_raw[];
@@ -144,6 +154,8 @@ __global__ __launch_bounds__(kThreadsPerGate *B) __attribute__((amdgpu_waves_per
 
     Lane ln;
     lane_init(ln, a.tables, L);
+    const __amdgpu_buffer_rsrc_t key_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<double2 *>(a.bk_fft), 0, (int)((size_t)a.n * 16 * kHalf * sizeof(double2)), 0x00020000);
 
     // ---- prologue ----
     {
@@ -215,8 +227,14 @@ __global__ __launch_bounds__(kThreadsPerGate *B) __attribute__((amdgpu_waves_per
 
         // ---- products with the key row: thread <-> slot, all gates of the workgroup ----
         {
-            const double2 *key = a.bk_fft + (size_t)i * 16 * kHalf;
-            for (int s = tid; s < kHalf; s += kThreadsPerGate * B) {
+            // key row i through a buffer descriptor: scalar base and row offset, 32-bit lane offset
+            const uint32_t row_bytes = (uint32_t)i * 16u * kHalf * (uint32_t)sizeof(double2);
+            constexpr int kSlotsPerThread = (kHalf + kThreadsPerGate * B - 1) / (kThreadsPerGate * B);
+#pragma unroll
+            for (int pass = 0; pass < kSlotsPerThread; ++pass) {
+                const int s = tid + pass * kThreadsPerGate * B;
+                if (kThreadsPerGate * B * kSlotsPerThread != kHalf && s >= kHalf) break;
+                const uint32_t voff = (uint32_t)s * (uint32_t)sizeof(double2);   // uniform base + 32-bit offset
                 double2 d[B][4];
 #pragma unroll
                 for (int q = 0; q < B; ++q)
@@ -229,18 +247,25 @@ __global__ __launch_bounds__(kThreadsPerGate *B) __attribute__((amdgpu_waves_per
 #pragma unroll
                     for (int r = 0; r < 4; ++r)
 #pragma unroll
-                        for (int o = 0; o < 2; ++o) k[r][o] = key[(r * 4 + 2 * half + o) * kHalf + s];
+                        for (int o = 0; o < 2; ++o)
+                            k[r][o] = load_key(key_rsrc, voff,
+                                               row_bytes + (uint32_t)((r * 4 + 2 * half + o) * kHalf * sizeof(double2)));
 #pragma unroll
                     for (int q = 0; q < B; ++q)
 #pragma unroll
                         for (int o = 0; o < 2; ++o) {
-                            double2 y = cmul(d[q][0], k[0][o]);
+                            // fused multiply-adds, two independent chains per part
+                            double yr = d[q][0].x * k[0][o].x, yi = d[q][0].x * k[0][o].y;
+                            double zr = -d[q][0].y * k[0][o].y, zi = d[q][0].y * k[0][o].x;
 #pragma unroll
                             for (int r = 1; r < 4; ++r) {
-                                y.x += d[q][r].x * k[r][o].x - d[q][r].y * k[r][o].y;
-                                y.y += d[q][r].x * k[r][o].y + d[q][r].y * k[r][o].x;
+                                yr = fma(d[q][r].x, k[r][o].x, yr);
+                                yi = fma(d[q][r].x, k[r][o].y, yi);
+                                zr = fma(-d[q][r].y, k[r][o].y, zr);
+                                zi = fma(d[q][r].y, k[r][o].x, zi);
                             }
-                            lds[q].spec[2 * half + o][s] = y;
+                            yr += zr; yi += zi;
+                            lds[q].spec[2 * half + o][s] = make_double2(yr, yi);
                         }
                 }
             }
