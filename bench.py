@@ -37,6 +37,9 @@ def main():
     ap.add_argument("--flat-count", type=int, default=65536)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--cpu-gates", type=int, default=512, help="gates in the oracle sample")
+    ap.add_argument("--copy-calibration-mib", type=int, default=0,
+                    help="after the timed steps, run one plain device-to-device copy of this size "
+                         "(a known-traffic kernel to scale rocprofv3's FETCH_SIZE / WRITE_SIZE by)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only; --gpus must be 1 "
@@ -97,6 +100,13 @@ def main():
     prof = T.tfhe_profile_read(ck, reset=True)
     T.tfhe_profile_enable(ck, False)
 
+    if args.copy_calibration_mib:
+        src = torch.ones(args.copy_calibration_mib << 18, dtype=torch.int32, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     elapsed = t1 - t0
     total_gates = gates_per_step * args.steps
     value = total_gates / elapsed
@@ -118,9 +128,15 @@ def main():
     gates_per_launch = prof["gates"] / br_launches
     flops_per_gate = FLOPS_PER_STEP * P.n
     achieved = flops_per_gate * gates_per_launch / (br_avg_ms * 1e-3) / 1e12 if br_avg_ms > 0 else 0.0
+    # HBM bytes per launch of that kernel, from the committed rocprofv3 counter summary (if one
+    # exists for this workload); the counters cannot be read from inside the process
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(tpath):
+        traffic = json.load(open(tpath)).get(args.workload, {}).get("blind_rotate_bytes_per_launch")
     roofline = {"bound": "alu", "achieved": round(achieved, 3), "peak": FP64_VECTOR_PEAK_TFLOPS,
                 "unit": "TFLOP/s", "frac": round(achieved / FP64_VECTOR_PEAK_TFLOPS, 4),
-                "traffic": None, "kernel": "blind_rotate_kernel",
+                "traffic": traffic, "kernel": "blind_rotate_kernel",
                 "avg_launch_ms": round(br_avg_ms, 4), "gates_per_launch": round(gates_per_launch, 1),
                 "flops_per_gate": flops_per_gate,
                 "kernel_ms": {"blind_rotate": round(prof["blind_rotate_ms"], 2),
