@@ -159,3 +159,54 @@ def test_bad_gate_records_are_rejected(gpu):
                 np.concatenate([rec(1, 3, 1, 2), rec(1, 0, 1, 3)])):      # reads a later record's output
         with pytest.raises(T.TfheError):
             T.tfhe_gate_stream(ck, bad, wires, 4)
+
+
+def test_other_parameter_set_general_key_switch(real_keys):
+    """n=300, Bgbit=8, key switch with 5 base-8 digits: exercises the one-gate-per-workgroup key
+    switch and the run-time gadget base, against an oracle key set of the same parameters."""
+    import torch
+    import paper_1806_03461_amd as T
+    from oracle import oracle as orc
+    P = T.Params(300, 1024, 1, 2, 8, 5, 3, -15, -25)
+    sk, ck = T.tfhe_keygen(P, 777)
+    keys = orc.Keys(orc.Params(300, 1024, 1, 2, 8, 5, 3, -15, -25), 777)
+    assert np.array_equal(T.tfhe_export_key(ck, T.KEY_KSK_RAW), keys.ksk)
+    a = np.array([0, 1, 1, 0, 1], np.uint8)
+    b = np.array([1, 1, 0, 0, 1], np.uint8)
+    cta, ctb = T.tfhe_encrypt(sk, 5, a), T.tfhe_encrypt(sk, 6, b)
+    for op in ("AND", "XNOR"):
+        da, db = T.to_device(cta), T.to_device(ctb)
+        out = torch.empty_like(da)
+        T.tfhe_gate_batch(ck, op, da, db, out, 5)
+        torch.cuda.synchronize()
+        got = T.to_host(out)
+        want = np.stack([keys.gate(op, cta[i], ctb[i]) for i in range(5)])
+        assert np.array_equal(got, want)
+        assert list(T.tfhe_decrypt(sk, got)) == [TRUTH[op](int(x), int(y)) for x, y in zip(a, b)]
+
+
+def test_results_do_not_depend_on_batching(gpu):
+    """The same gates evaluated twice, in another order, and as a gate stream split over several
+    depths give identical bytes: no result depends on which workgroup or launch computed it."""
+    import torch
+    T, sk, ck = gpu
+    rng = np.random.default_rng(13)
+    cnt = 300
+    a, b = rng.integers(0, 2, cnt).astype(np.uint8), rng.integers(0, 2, cnt).astype(np.uint8)
+    cta, ctb = T.tfhe_encrypt(sk, 81, a), T.tfhe_encrypt(sk, 82, b)
+    first = run_batch(T, ck, "AND", cta, ctb)
+    assert np.array_equal(first, run_batch(T, ck, "AND", cta, ctb))
+    perm = rng.permutation(cnt)
+    assert np.array_equal(first[perm], run_batch(T, ck, "AND", cta[perm], ctb[perm]))
+    # as a stream: wires = [a | b | out], records in reverse order
+    wires = torch.zeros((3 * cnt, 501), dtype=torch.int32, device="cuda")
+    wires[:cnt], wires[cnt:2 * cnt] = T.to_device(cta), T.to_device(ctb)
+    recs = np.array([(T.AND, 0, 0, 0, i, cnt + i, 2 * cnt + i) for i in reversed(range(cnt))], dtype=T.GATE_DTYPE)
+    T.tfhe_profile_enable(ck, True)
+    T.tfhe_profile_read(ck, reset=True)
+    T.tfhe_gate_stream(ck, recs, wires, 3 * cnt)
+    torch.cuda.synchronize()
+    prof = T.tfhe_profile_read(ck, reset=True)
+    T.tfhe_profile_enable(ck, False)
+    assert np.array_equal(T.to_host(wires[2 * cnt:]), first)
+    assert prof["gates"] == cnt and prof["blind_rotate_launches"] == 1 and prof["blind_rotate_ms"] > 0
