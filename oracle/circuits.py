@@ -39,6 +39,14 @@ class Circuit:
         self.gates.append((OP[op], a[1], b[1], 0, a[0], b[0], out))
         return (out, 0)
 
+    def mux(self, sel, a, b):
+        """sel ? a : b as the two-record multiplexer (same selector and output wire)."""
+        out = self.n_wires
+        self.n_wires += 1
+        self.gates.append((OP["MUX"], sel[1], a[1], 0, sel[0], a[0], out))
+        self.gates.append((OP["MUX_ELSE"], sel[1], b[1], 0, sel[0], b[0], out))
+        return (out, 0)
+
     def gate_array(self):
         return np.array(self.gates, dtype=GATE_DTYPE)
 
@@ -113,7 +121,27 @@ def threshold_chain(cir, number, T):
     return o
 
 
-def neuron(cir, x_literals, w_row, T, out_bits=0):
+def threshold_chain_mux(cir, number, T):
+    """Algorithm 1 as printed: one MUX per bit of S, least significant first,
+    o = MUX(S_i, 1, o) for a 0 threshold bit and o = MUX(S_i, o, 0) for a 1 bit, the constants
+    being noiseless encryptions.  The printed initial value o = 0 would give S > T; the stated
+    output is 2S >= d - b, so the chain starts from o = 1 here as well."""
+    bits, m = number
+    one, zero = (cir.c1, 0), (cir.c0, 0)
+    o = one
+    for i, s in enumerate(bits):
+        if (T >> i) & 1:
+            o = cir.mux(s, o, zero)
+        else:
+            o = cir.mux(s, one, o)
+    if T < 0:
+        return CONST1
+    if T >> len(bits):
+        return CONST0
+    return o
+
+
+def neuron(cir, x_literals, w_row, T, out_bits=0, comparator="folded"):
     """One output unit.  x_literals[i] is the literal of input i; w in {-1,0,+1}.
     Returns one literal/constant (T given) or out_bits popcount literals (T None)."""
     leaves = []
@@ -124,19 +152,21 @@ def neuron(cir, x_literals, w_row, T, out_bits=0):
             leaves.append((lit[0], lit[1] ^ 1))
     S = popcount_tree(cir, leaves)
     if T is not None:
+        if comparator == "mux":
+            return [threshold_chain_mux(cir, S, int(T))]
         return [threshold_chain(cir, S, int(T))]
     bits = list(S[0]) + [CONST0] * max(0, out_bits - len(S[0]))
     assert len(bits) == out_bits, "out_bits too small for this popcount"
     return bits
 
 
-def dense_layer(d, W, T, out_bits=0):
+def dense_layer(d, W, T, out_bits=0, comparator="folded"):
     """Circuit of a fully connected layer.  Returns (circuit, outputs)."""
     cir = Circuit(d)
     x = [(i, 0) for i in range(d)]
     outs = []
     for j in range(W.shape[0]):
-        outs += neuron(cir, x, W[j], None if T is None else T[j], out_bits)
+        outs += neuron(cir, x, W[j], None if T is None else T[j], out_bits, comparator)
     return cir, outs
 
 
@@ -183,8 +213,15 @@ def eval_plain(cir, in_bits, outs):
     w = np.zeros(cir.n_wires, np.uint8)
     w[:cir.n_inputs] = in_bits
     w[cir.c0], w[cir.c1] = 0, 1
+    pending = None
     for (op, n0, n1, _, i0, i1, o) in cir.gates:
-        w[o] = _TRUTH[op](int(w[i0]) ^ n0, int(w[i1]) ^ n1)
+        if op == OP["MUX"]:
+            pending = (int(w[i0]) ^ n0, int(w[i1]) ^ n1)        # selector, value if selected
+        elif op == OP["MUX_ELSE"]:
+            sel, a = pending
+            w[o] = a if sel else int(w[i1]) ^ n1
+        else:
+            w[o] = _TRUTH[op](int(w[i0]) ^ n0, int(w[i1]) ^ n1)
     res = []
     for lit in outs:
         if lit is CONST0:

@@ -11,7 +11,7 @@ import numpy as np
 
 from . import build_oracle
 
-OP = {"NAND": 0, "AND": 1, "OR": 2, "NOR": 3, "XOR": 4, "XNOR": 5}
+OP = {"NAND": 0, "AND": 1, "OR": 2, "NOR": 3, "XOR": 4, "XNOR": 5, "MUX": 6, "MUX_ELSE": 7}
 
 DOMAIN = {"RAW": 0, "LWE_SK": 1, "TRLWE_SK": 2, "BK_A": 3, "BK_E": 4,
           "KSK_A": 5, "KSK_E": 6, "ENC_A": 7, "ENC_E": 8}
@@ -90,6 +90,9 @@ def lib():
         L.orc_key_switch.argtypes = [PP, u32p, u32p, u32p]
         L.orc_gate.argtypes = [PP, u32p, u32p, C.c_int, u32p, C.c_int, u32p, C.c_int, u32p]
         L.orc_gate_batch.argtypes = [PP, u32p, u32p, C.c_void_p, C.c_size_t, u32p, C.c_int]
+        L.orc_bootstrap_extract.restype = None
+        L.orc_bootstrap_extract.argtypes = [PP, u32p, u32p, u32p]
+        L.orc_mux.argtypes = [PP, u32p, u32p, u32p, C.c_int, u32p, C.c_int, u32p, C.c_int, u32p]
     return _lib
 
 
@@ -170,6 +173,18 @@ class Keys:
             raise ValueError("bad gate op")
         return out
 
+    def mux(self, s, a, b, negs=0, nega=0, negb=0):
+        """s ? a : b  (two blind rotations, one key switch)."""
+        out = np.empty(self.P.n + 1, np.uint32)
+        f = lambda x: np.ascontiguousarray(x, np.uint32)
+        lib().orc_mux(C.byref(self.P), self.bk, self.ksk, f(s), negs, f(a), nega, f(b), negb, out)
+        return out
+
+    def bootstrap_extract(self, c):
+        ext = np.empty(self.P.N + 1, np.uint32)
+        lib().orc_bootstrap_extract(C.byref(self.P), self.bk, np.ascontiguousarray(c, np.uint32), ext)
+        return ext
+
     def precombine(self, op, c0, c1, neg0=0, neg1=0):
         out = np.empty(self.P.n + 1, np.uint32)
         rc = lib().orc_gate_precombine(C.byref(self.P), OP[op] if isinstance(op, str) else op,
@@ -247,6 +262,10 @@ def levelize(gates, nwires):
     lv = np.zeros(len(gates), np.int64)
     for i, g in enumerate(gates):
         d = 1 + max(depth[g["in0"]], depth[g["in1"]])
+        if g["op"] == OP["MUX"]:                       # both halves of a multiplexer share a level
+            d = max(d, 1 + depth[gates[i + 1]["in1"]])
+        elif g["op"] == OP["MUX_ELSE"]:
+            d = lv[i - 1]
         depth[g["out"]] = d
         lv[i] = d
     return [np.nonzero(lv == d)[0] for d in range(1, int(lv.max(initial=0)) + 1)]

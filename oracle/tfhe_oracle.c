@@ -460,6 +460,47 @@ int orc_gate(const orc_params *P, const uint32_t *bk, const uint32_t *ksk, int o
     return rc;
 }
 
+/*
+ * Steps 2-5 on an already pre-combined sample: the bootstrapped value as an LWE sample under the
+ * ring key (N+1 words), not yet key-switched.
+ */
+void orc_bootstrap_extract(const orc_params *P, const uint32_t *bk, const uint32_t *c, uint32_t *ext)
+{
+    const int n = P->n, N = P->N;
+    uint32_t *bar = (uint32_t *)malloc(sizeof(uint32_t) * ((size_t)(n + 1) + 2 * N));
+    uint32_t *acc = bar + (n + 1);
+    orc_modswitch(P, c, bar);
+    orc_acc_init(P, bar[n], acc);
+    orc_blind_rotate(P, bk, bar, acc);
+    orc_sample_extract(P, acc, ext);
+    free(bar);
+}
+
+/*
+ * Multiplexer MUX(s, a, b) = s ? a : b, the three-input gate of Algorithm 1 (TAPAS Sec. 4.1;
+ * "MUX(s, a, b) returns a if s = 1 and b otherwise").  CGGI evaluates it with two blind
+ * rotations and one key switch: u1 = bootstrap(AND(s, a)), u2 = bootstrap(AND(NOT s, b)), both
+ * left under the ring key; exactly one or none of them is true, so u1 + u2 + 1/8 is +-1/8 and
+ * is key-switched once.  neg flags take an input negated, as for the two-input gates.
+ */
+int orc_mux(const orc_params *P, const uint32_t *bk, const uint32_t *ksk,
+            const uint32_t *s, int negs, const uint32_t *a, int nega, const uint32_t *b, int negb,
+            uint32_t *out)
+{
+    const int n = P->n, N = P->N;
+    uint32_t *c = (uint32_t *)malloc(sizeof(uint32_t) * ((size_t)(n + 1) + 2 * (N + 1)));
+    uint32_t *u1 = c + (n + 1), *u2 = u1 + (N + 1);
+    orc_gate_precombine(P, OP_AND, s, negs, a, nega, c);
+    orc_bootstrap_extract(P, bk, c, u1);
+    orc_gate_precombine(P, OP_AND, s, !negs, b, negb, c);
+    orc_bootstrap_extract(P, bk, c, u2);
+    for (int j = 0; j <= N; ++j) u1[j] += u2[j];
+    u1[N] += MU;
+    orc_key_switch(P, ksk, u1, out);
+    free(c);
+    return 0;
+}
+
 /* gate record shared by the batch entry point: 16 bytes */
 typedef struct { uint8_t op, neg0, neg1, pad; int32_t in0, in1, out; } orc_gate_rec;
 
@@ -467,7 +508,11 @@ typedef struct { uint8_t op, neg0, neg1, pad; int32_t in0, in1, out; } orc_gate_
  * Evaluate `count` mutually independent gates over a wire array
  * (wires[w] is an LWE sample of n+1 words).  Gates are independent, so the
  * loop may run on several threads; each gate is still the plain orc_gate.
+ * A multiplexer is two consecutive records with the same selector and output:
+ * {OP_MUX, negs, nega, s, a, out} then {OP_MUX_ELSE, negs, negb, s, b, out}.
  */
+enum { OP_MUX = 6, OP_MUX_ELSE = 7 };
+
 int orc_gate_batch(const orc_params *P, const uint32_t *bk, const uint32_t *ksk,
                    const orc_gate_rec *g, size_t count, uint32_t *wires, int threads)
 {
@@ -476,8 +521,20 @@ int orc_gate_batch(const orc_params *P, const uint32_t *bk, const uint32_t *ksk,
     if (threads < 1) threads = 1;
 #pragma omp parallel for schedule(dynamic, 1) num_threads(threads)
     for (long i = 0; i < (long)count; ++i) {
-        int rc = orc_gate(P, bk, ksk, g[i].op, wires + g[i].in0 * w, g[i].neg0,
+        int rc = 0;
+        if (g[i].op == OP_MUX_ELSE) {
+            if (i == 0 || g[i - 1].op != OP_MUX) rc = -2;      /* evaluated with its first half */
+        } else if (g[i].op == OP_MUX) {
+            if (i + 1 >= (long)count || g[i + 1].op != OP_MUX_ELSE || g[i + 1].in0 != g[i].in0 ||
+                g[i + 1].out != g[i].out || g[i + 1].neg0 != g[i].neg0)
+                rc = -2;
+            else
+                rc = orc_mux(P, bk, ksk, wires + g[i].in0 * w, g[i].neg0, wires + g[i].in1 * w, g[i].neg1,
+                             wires + g[i + 1].in1 * w, g[i + 1].neg1, wires + g[i].out * w);
+        } else {
+            rc = orc_gate(P, bk, ksk, g[i].op, wires + g[i].in0 * w, g[i].neg0,
                           wires + g[i].in1 * w, g[i].neg1, wires + g[i].out * w);
+        }
         if (rc) {
 #pragma omp atomic write
             bad = 1;

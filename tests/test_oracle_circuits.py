@@ -212,3 +212,33 @@ def test_one_neuron_encrypted_real_parameters(orc, real_keys):
         cir, outs = cc.dense_layer(d, W, np.array([T]))
         res, _ = cc.eval_encrypted(real_keys, cir, ct, outs, threads=8)
         assert real_keys.decrypt(res)[0] == cc.dense_plain(x, W, np.array([T]))[0]
+
+
+# --------------------------------------------------------------------------- Algorithm 1 as printed
+@pytest.mark.parametrize("m", [1, 2, 3, 5, 8, 13, 31, 32])
+def test_mux_comparator_all_S_all_T(m):
+    w = int(m).bit_length()
+    tree = len(popcount_bits(m)[0].gates)
+    for T in range(-1, m + 3):
+        cir = cc.Circuit(m)
+        outs = cc.neuron(cir, [(i, 0) for i in range(m)], np.ones(m, np.int8), T, comparator="mux")
+        assert len(cir.gates) == tree + 2 * w              # one MUX (two records) per bit of S
+        for S in range(m + 1):
+            x = np.zeros(m, np.uint8)
+            x[:S] = 1
+            assert cc.eval_plain(cir, x, outs)[0] == (1 if S >= T else 0), (m, T, S)
+
+
+def test_mux_comparator_encrypted_toy(orc, toy_keys):
+    rng = np.random.default_rng(21)
+    d = 7
+    W = (2 * rng.integers(0, 2, (2, d)) - 1).astype(np.int8)
+    T = np.array([3, 5], np.int32)
+    x = rng.integers(0, 2, d).astype(np.uint8)
+    ct = toy_keys.encrypt(x, 4)
+    cir, outs = cc.dense_layer(d, W, T, comparator="mux")
+    res, _ = cc.eval_encrypted(toy_keys, cir, ct, outs, threads=4)
+    assert np.array_equal(toy_keys.decrypt(res), cc.dense_plain(x, W, T))
+    folded, fo = cc.dense_layer(d, W, T)
+    ref, _ = cc.eval_encrypted(toy_keys, folded, ct, fo, threads=4)
+    assert np.array_equal(toy_keys.decrypt(ref), toy_keys.decrypt(res))

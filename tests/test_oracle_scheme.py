@@ -245,3 +245,48 @@ def test_real_parameter_truth_tables_and_noise(orc, real_keys):
         g = gates[k]
         assert np.array_equal(K.gate(int(g["op"]), ct[g["in0"]], ct[g["in1"]], int(g["neg0"]), int(g["neg1"])),
                               out[k])
+
+
+# --------------------------------------------------------------------------- multiplexer
+def test_mux_truth_table_toy_and_real(orc, toy_keys, real_keys):
+    """MUX(s, a, b) = a if s else b (Sec. 4.1) for all eight inputs and negation flags."""
+    for K, flags in ((toy_keys, list(itertools.product((0, 1), repeat=3))), (real_keys, [(0, 0, 0), (1, 0, 1)])):
+        ct = K.encrypt(np.array([0, 1], np.uint8), 17)
+        for s, a, b in itertools.product((0, 1), repeat=3):
+            for ns, na, nb in flags:
+                got = K.decrypt(K.mux(ct[s], ct[a], ct[b], ns, na, nb))[0]
+                assert got == ((a ^ na) if (s ^ ns) else (b ^ nb)), (s, a, b, ns, na, nb)
+
+
+def test_mux_is_two_bootstraps_summed_then_switched(orc, toy_keys):
+    """phase_S(u1 + u2 + 1/8) is +-1/8 with the sign of the selected input, where u1, u2 are the
+    ring-key samples of AND(s, a) and AND(NOT s, b); MUX key-switches exactly that sum."""
+    K, N = toy_keys, toy_keys.P.N
+    ct = K.encrypt(np.array([0, 1], np.uint8), 18)
+    for s, a, b in itertools.product((0, 1), repeat=3):
+        u1 = K.bootstrap_extract(K.precombine("AND", ct[s], ct[a]))
+        u2 = K.bootstrap_extract(K.precombine("AND", ct[s], ct[b], 1, 0))
+        u = (u1 + u2).astype(np.uint32)
+        u[N] = (int(u[N]) + MU) & M32
+        ph = int(s32((int(u[N]) - int((u[:N].astype(np.int64) * K.trlwe_sk).sum())) & M32))
+        want = a if s else b
+        assert abs(abs(ph) - MU) < MU // 4 and (ph > 0) == bool(want)
+        assert np.array_equal(K.key_switch(u), K.mux(ct[s], ct[a], ct[b]))
+
+
+def test_mux_batch_records_match_scalar_entry_point(orc, toy_keys):
+    K = toy_keys
+    bits = np.array([0, 1, 1, 0], np.uint8)
+    ct = K.encrypt(bits, 19)
+    n1 = K.P.n + 1
+    wires = np.zeros((8, n1), np.uint32)
+    wires[:4] = ct
+    recs = np.array([(orc.OP["MUX"], 0, 0, 0, 1, 2, 4), (orc.OP["MUX_ELSE"], 0, 1, 0, 1, 3, 4),
+                     (orc.OP["AND"], 0, 0, 0, 1, 2, 5),
+                     (orc.OP["MUX"], 1, 0, 0, 0, 3, 6), (orc.OP["MUX_ELSE"], 1, 0, 0, 0, 1, 6)], dtype=orc.GATE_DTYPE)
+    K.gate_batch(recs, wires, threads=3)
+    assert np.array_equal(wires[4], K.mux(ct[1], ct[2], ct[3], 0, 0, 1))
+    assert np.array_equal(wires[5], K.gate("AND", ct[1], ct[2]))
+    assert np.array_equal(wires[6], K.mux(ct[0], ct[3], ct[1], 1, 0, 0))
+    with pytest.raises(ValueError):                      # a lone first half is malformed
+        K.gate_batch(recs[:1], wires, threads=1)
