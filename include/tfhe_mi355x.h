@@ -70,7 +70,13 @@ typedef struct tfhe_cloud_key tfhe_cloud_key;
 
 /* Gate opcodes.  The paper's circuits use XNOR, AND, OR (Sec. 4.1.1); the other
  * three come from the same mechanism with different constants. */
-enum { TFHE_NAND = 0, TFHE_AND = 1, TFHE_OR = 2, TFHE_NOR = 3, TFHE_XOR = 4, TFHE_XNOR = 5 };
+enum { TFHE_NAND = 0, TFHE_AND = 1, TFHE_OR = 2, TFHE_NOR = 3, TFHE_XOR = 4, TFHE_XNOR = 5,
+       /* The three-input multiplexer of Algorithm 1, MUX(s, a, b) = a if s = 1 and b otherwise
+        * (Sec. 4.1.1; "a dedicated implementation in TFHE"): two blind rotations -- AND(s, a) and
+        * AND(NOT s, b) -- whose sum plus 1/8 is key-switched once.  In a gate stream it is two
+        * consecutive records with the same selector, selector flag and output wire:
+        *   {TFHE_MUX, negs, nega, s, a, out}  {TFHE_MUX_ELSE, negs, negb, s, b, out}. */
+       TFHE_MUX = 6, TFHE_MUX_ELSE = 7 };
 
 /* One gate of a circuit over a wire array: wires[out] = op(+-wires[in0], +-wires[in1]).
  * neg0 / neg1 = 1 takes that input negated: this is how an XNOR with a plaintext
@@ -138,6 +144,11 @@ int tfhe_cloud_key_upload(tfhe_cloud_key *ck);
 int tfhe_gate_batch(tfhe_cloud_key *ck, int op, const uint32_t *a, const uint32_t *b,
                     uint32_t *out, size_t count, void *stream);
 
+/* count independent multiplexers: out[i] = s[i] ? a[i] : b[i].  All buffers DEVICE [count][n+1];
+ * out may be the same buffer as s, a or b (exactly). */
+int tfhe_mux_batch(tfhe_cloud_key *ck, const uint32_t *s, const uint32_t *a, const uint32_t *b,
+                   uint32_t *out, size_t count, void *stream);
+
 /* A circuit of mixed gates over a wire array (Sec. 4: "gates at the same level in the
  * tree representation of the circuit can be evaluated in parallel").  gates: HOST,
  * topologically ordered (an input is either never written or written by an earlier
@@ -157,6 +168,19 @@ int tfhe_gate_stream(tfhe_cloud_key *ck, const tfhe_gate_rec *gates, size_t ngat
 int bnn_dense_lower(int d, const int8_t *W, const int32_t *T, int p, int out_bits,
                     tfhe_gate_rec **gates, size_t *ngates, tfhe_out_ref **outs, size_t *nouts,
                     size_t *nwires);
+
+/* Lowering options (flags of the *_opts entry points). */
+enum { TFHE_LOWER_DEFAULT = 0,
+       /* comparator exactly as Algorithm 1 prints it: one MUX gate per bit of S with noiseless
+        * constants as data inputs (started from o = 1, see bnn_dense_lower), instead of the chain
+        * folded to AND / OR gates by the plaintext threshold bits */
+       TFHE_LOWER_MUX_COMPARATOR = 1 };
+int bnn_dense_lower_opts(int d, const int8_t *W, const int32_t *T, int p, int out_bits, uint32_t flags,
+                         tfhe_gate_rec **gates, size_t *ngates, tfhe_out_ref **outs, size_t *nouts,
+                         size_t *nwires);
+int bnn_dense_encrypted_opts(tfhe_cloud_key *ck, const uint32_t *x, int d, const int8_t *W,
+                             const int32_t *T, int p, uint32_t *out, int out_bits, uint32_t flags,
+                             void *stream);
 
 /* Same for a convolution (Sec. 4: "fully connected, convolutional").  x is [C][H][Wd];
  * K: HOST int8 [O][C][kh][kw]; T: HOST int32 [O] (one threshold per output channel).

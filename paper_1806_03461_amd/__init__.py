@@ -13,8 +13,9 @@ import numpy as np
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libtfhe_mi355x.so")
 
-NAND, AND, OR, NOR, XOR, XNOR = range(6)
+NAND, AND, OR, NOR, XOR, XNOR, MUX, MUX_ELSE = range(8)
 OPS = {"NAND": NAND, "AND": AND, "OR": OR, "NOR": NOR, "XOR": XOR, "XNOR": XNOR}
+LOWER_DEFAULT, LOWER_MUX_COMPARATOR = 0, 1
 KEY_LWE_SK, KEY_TRLWE_SK, KEY_BK_RAW, KEY_KSK_RAW = range(4)
 
 GATE_DTYPE = np.dtype([("op", "u1"), ("neg0", "u1"), ("neg1", "u1"), ("pad", "u1"),
@@ -43,7 +44,8 @@ class Profile(C.Structure):
 EXPORTS = ["tfhe_last_error", "tfhe_default_params", "tfhe_keygen", "tfhe_encrypt", "tfhe_decrypt",
            "tfhe_trivial", "tfhe_export_key", "tfhe_get_params", "tfhe_free_secret_key",
            "tfhe_free_cloud_key", "tfhe_free_buffer", "tfhe_cloud_key_upload", "tfhe_gate_batch",
-           "tfhe_gate_stream", "bnn_dense_lower", "bnn_conv_lower", "bnn_dense_encrypted",
+           "tfhe_mux_batch", "tfhe_gate_stream", "bnn_dense_lower", "bnn_dense_lower_opts", "bnn_conv_lower",
+           "bnn_dense_encrypted", "bnn_dense_encrypted_opts",
            "bnn_conv_encrypted", "tfhe_profile_enable", "tfhe_profile_read",
            "tfhe_rounding_margin_enable", "tfhe_rounding_margin_read"]
 
@@ -75,9 +77,12 @@ def lib():
         L.tfhe_free_buffer.restype = None
         L.tfhe_cloud_key_upload.argtypes = [vp]
         L.tfhe_gate_batch.argtypes = [vp, i32, vp, vp, vp, sz, vp]
+        L.tfhe_mux_batch.argtypes = [vp, vp, vp, vp, vp, sz, vp]
         L.tfhe_gate_stream.argtypes = [vp, vp, sz, vp, sz, vp]
         lower_tail = [C.POINTER(vp), C.POINTER(sz), C.POINTER(vp), C.POINTER(sz), C.POINTER(sz)]
         L.bnn_dense_lower.argtypes = [i32, vp, vp, i32, i32] + lower_tail
+        L.bnn_dense_lower_opts.argtypes = [i32, vp, vp, i32, i32, C.c_uint32] + lower_tail
+        L.bnn_dense_encrypted_opts.argtypes = [vp, vp, i32, vp, vp, i32, vp, i32, C.c_uint32, vp]
         L.bnn_conv_lower.argtypes = [i32, i32, i32, vp, i32, i32, i32, i32, i32, vp] + lower_tail
         L.bnn_dense_encrypted.argtypes = [vp, vp, i32, vp, vp, i32, vp, i32, vp]
         L.bnn_conv_encrypted.argtypes = [vp, vp, i32, i32, i32, vp, i32, i32, i32, i32, i32, vp, vp, vp]
@@ -192,6 +197,11 @@ def tfhe_gate_batch(ck, op, a, b, out, count, stream=None):
     _check(lib().tfhe_gate_batch(ck.handle, op, _dev_ptr(a), _dev_ptr(b), _dev_ptr(out), count, _stream(stream)))
 
 
+def tfhe_mux_batch(ck, s, a, b, out, count, stream=None):
+    _check(lib().tfhe_mux_batch(ck.handle, _dev_ptr(s), _dev_ptr(a), _dev_ptr(b), _dev_ptr(out), count,
+                                _stream(stream)))
+
+
 def tfhe_gate_stream(ck, gates, wires, nwires, stream=None):
     gates = _host(gates, GATE_DTYPE)
     _check(lib().tfhe_gate_stream(ck.handle, gates.ctypes.data, gates.size, _dev_ptr(wires), nwires,
@@ -206,6 +216,16 @@ def _take(ptr, count, dtype):
         arr = np.frombuffer((C.c_char * (n * dtype.itemsize)).from_address(ptr.value), dtype=dtype).copy()
     lib().tfhe_free_buffer(ptr)
     return arr
+
+
+def bnn_dense_lower_opts(d, W, T, p, out_bits=0, flags=0):
+    W = _host(W, np.int8)
+    Tp = None if T is None else _host(T, np.int32)
+    g, o = C.c_void_p(), C.c_void_p()
+    ng, no, nw = C.c_size_t(), C.c_size_t(), C.c_size_t()
+    _check(lib().bnn_dense_lower_opts(d, W.ctypes.data, None if Tp is None else Tp.ctypes.data, p, out_bits,
+                                      flags, C.byref(g), C.byref(ng), C.byref(o), C.byref(no), C.byref(nw)))
+    return _take(g, ng, GATE_DTYPE), _take(o, no, OUT_DTYPE), nw.value
 
 
 def bnn_dense_lower(d, W, T, p, out_bits=0):
@@ -235,6 +255,14 @@ def bnn_dense_encrypted(ck, x, d, W, T, p, out, out_bits=0, stream=None):
     _check(lib().bnn_dense_encrypted(ck.handle, _dev_ptr(x), d, W.ctypes.data,
                                      None if Tp is None else Tp.ctypes.data, p, _dev_ptr(out), out_bits,
                                      _stream(stream)))
+
+
+def bnn_dense_encrypted_opts(ck, x, d, W, T, p, out, out_bits=0, flags=0, stream=None):
+    W = _host(W, np.int8)
+    Tp = None if T is None else _host(T, np.int32)
+    _check(lib().bnn_dense_encrypted_opts(ck.handle, _dev_ptr(x), d, W.ctypes.data,
+                                          None if Tp is None else Tp.ctypes.data, p, _dev_ptr(out), out_bits,
+                                          flags, _stream(stream)))
 
 
 def bnn_conv_encrypted(ck, x, C_, H, Wd, K, T, stride, pad, out, stream=None):

@@ -56,6 +56,17 @@ public:
         return Sig::of(r.out);
     }
 
+    // sel ? a : b as the two-record multiplexer
+    Sig emit_mux(Sig sel, Sig a, Sig b) {
+        tfhe_gate_rec r{};
+        r.op = TFHE_MUX; r.neg0 = (uint8_t)sel.flag; r.neg1 = (uint8_t)a.flag;
+        r.in0 = sel.wire; r.in1 = a.wire; r.out = next_++;
+        gates_.push_back(r);
+        r.op = TFHE_MUX_ELSE; r.neg1 = (uint8_t)b.flag; r.in1 = b.wire;
+        gates_.push_back(r);
+        return Sig::of(r.out);
+    }
+
     static int width_of(int64_t bound) { int w = 0; while (bound >> w) ++w; return w; }
 
     // Ripple-carry addition; carries are produced only where the bounds allow one.
@@ -126,9 +137,20 @@ public:
         return o;
     }
 
+    // [S >= T] with one multiplexer per bit of S, as Algorithm 1 prints it (started from 1)
+    Sig at_least_by_mux(const Number &S, int64_t T) {
+        const Sig one = Sig::of(one_), zero = Sig::of(zero_);
+        Sig o = one;
+        for (size_t pos = 0; pos < S.bits.size(); ++pos)
+            o = ((T >> pos) & 1) ? emit_mux(S.bits[pos], o, zero) : emit_mux(S.bits[pos], one, o);
+        if (T < 0) return Sig::constant(1);
+        if (T >> S.bits.size()) return Sig::constant(0);
+        return o;
+    }
+
     // one output unit over the listed inputs
     void unit(const std::vector<Sig> &inputs, const int8_t *w, const int32_t *T, int out_bits,
-              std::vector<tfhe_out_ref> &outs) {
+              std::vector<tfhe_out_ref> &outs, uint32_t flags = 0) {
         std::vector<Sig> leaves;
         leaves.reserve(inputs.size());
         for (size_t i = 0; i < inputs.size(); ++i) {
@@ -139,7 +161,7 @@ public:
         }
         const Number S = popcount(leaves);
         if (T) {
-            const Sig o = at_least(S, *T);
+            const Sig o = (flags & TFHE_LOWER_MUX_COMPARATOR) ? at_least_by_mux(S, *T) : at_least(S, *T);
             outs.push_back(tfhe_out_ref{o.wire, o.flag});
         } else {
             for (int bpos = 0; bpos < out_bits; ++bpos) {
@@ -169,8 +191,9 @@ int check_weights(const int8_t *W, size_t count) {
     return TFHE_OK;
 }
 
-int lower_dense(int d, const int8_t *W, const int32_t *T, int p, int out_bits, Builder &b,
+int lower_dense(int d, const int8_t *W, const int32_t *T, int p, int out_bits, uint32_t flags, Builder &b,
                 std::vector<tfhe_out_ref> &outs) {
+    if (flags & ~(uint32_t)TFHE_LOWER_MUX_COMPARATOR) return set_error(TFHE_E_PARAM, "unknown lowering flags %u", flags);
     if (d < 1 || p < 1) return set_error(TFHE_E_SIZE, "layer sizes must be positive");
     if (!W) return set_error(TFHE_E_NULL, "W is NULL");
     if (!T) {
@@ -187,7 +210,7 @@ int lower_dense(int d, const int8_t *W, const int32_t *T, int p, int out_bits, B
     if (int rc = check_weights(W, (size_t)d * p)) return rc;
     std::vector<Sig> x(d);
     for (int i = 0; i < d; ++i) x[i] = Sig::of(i);
-    for (int j = 0; j < p; ++j) b.unit(x, W + (size_t)j * d, T ? T + j : nullptr, out_bits, outs);
+    for (int j = 0; j < p; ++j) b.unit(x, W + (size_t)j * d, T ? T + j : nullptr, out_bits, outs, flags);
     return TFHE_OK;
 }
 
@@ -241,10 +264,17 @@ extern "C" {
 
 int bnn_dense_lower(int d, const int8_t *W, const int32_t *T, int p, int out_bits, tfhe_gate_rec **gates,
                     size_t *ngates, tfhe_out_ref **outs, size_t *nouts, size_t *nwires) {
+    return bnn_dense_lower_opts(d, W, T, p, out_bits, TFHE_LOWER_DEFAULT, gates, ngates, outs, nouts, nwires);
+}
+
+int bnn_dense_lower_opts(int d, const int8_t *W, const int32_t *T, int p, int out_bits, uint32_t flags,
+                         tfhe_gate_rec **gates, size_t *ngates, tfhe_out_ref **outs, size_t *nouts,
+                         size_t *nwires) {
     if (!gates || !ngates || !outs || !nouts || !nwires) return set_error(TFHE_E_NULL, "NULL output pointer");
+    if (d < 1) return set_error(TFHE_E_SIZE, "layer sizes must be positive");
     Builder b(d);
     std::vector<tfhe_out_ref> o;
-    if (int rc = lower_dense(d, W, T, p, out_bits, b, o)) return rc;
+    if (int rc = lower_dense(d, W, T, p, out_bits, flags, b, o)) return rc;
     if (int rc = hand_over(b.gates(), gates, ngates)) return rc;
     if (int rc = hand_over(o, outs, nouts)) { free(*gates); return rc; }
     *nwires = (size_t)b.wires();
@@ -267,11 +297,17 @@ int bnn_conv_lower(int C, int H, int Wd, const int8_t *K, int O, int kh, int kw,
 
 int bnn_dense_encrypted(tfhe_cloud_key *ck, const uint32_t *x, int d, const int8_t *W, const int32_t *T, int p,
                         uint32_t *out, int out_bits, void *stream) {
+    return bnn_dense_encrypted_opts(ck, x, d, W, T, p, out, out_bits, TFHE_LOWER_DEFAULT, stream);
+}
+
+int bnn_dense_encrypted_opts(tfhe_cloud_key *ck, const uint32_t *x, int d, const int8_t *W, const int32_t *T,
+                             int p, uint32_t *out, int out_bits, uint32_t flags, void *stream) {
     if (int rc = tfhe::ensure_uploaded(ck)) return rc;
     if (!x || !out) return set_error(TFHE_E_NULL, "NULL ciphertext buffer");
+    if (d < 1) return set_error(TFHE_E_SIZE, "layer sizes must be positive");
     Builder b(d);
     std::vector<tfhe_out_ref> o;
-    if (int rc = lower_dense(d, W, T, p, out_bits, b, o)) return rc;
+    if (int rc = lower_dense(d, W, T, p, out_bits, flags, b, o)) return rc;
     return evaluate(ck, b, o, x, d, out, (hipStream_t)stream);
 }
 

@@ -87,11 +87,13 @@ int end_timed(tfhe_cloud_key *ck, hipStream_t stream, TimedLaunch &tl) {
 }
 
 // One batch of `count` gates: blind rotation into the extract workspace, then key switch.
+// `count` counts launch items: a multiplexer is two of them (its two blind rotations).
 int run_batch(tfhe_cloud_key *ck, const tfhe_gate_rec *d_recs, int uniform_op, const uint32_t *in0,
-              const uint32_t *in1, uint32_t *out, size_t count, hipStream_t stream) {
+              const uint32_t *in1, const uint32_t *in1_alt, uint32_t *out, size_t count, bool has_mux,
+              hipStream_t stream) {
     const tfhe_params &P = ck->params;
     BlindRotateArgs br{};
-    br.recs = d_recs; br.uniform_op = uniform_op; br.in0 = in0; br.in1 = in1;
+    br.recs = d_recs; br.uniform_op = uniform_op; br.in0 = in0; br.in1 = in1; br.in1_alt = in1_alt;
     br.ext = (uint32_t *)ck->ws_ext.ptr; br.count = count;
     br.bk_fft = ck->d_bk_fft; br.tables = ck->d_tables; br.n = P.n; br.bgbit = P.bk_Bgbit;
     br.margin = ck->margin ? ck->d_margin : nullptr;
@@ -99,11 +101,13 @@ int run_batch(tfhe_cloud_key *ck, const tfhe_gate_rec *d_recs, int uniform_op, c
     ks.ext = br.ext; ks.recs = d_recs; ks.out = out; ks.count = count; ks.ksk = ck->d_ksk;
     ks.n = P.n; ks.t = P.ks_t; ks.basebit = P.ks_basebit; ks.stride = (P.n + 2) & ~1;
     ks.group = key_switch_group(count);
+    ks.uniform_mux = !d_recs && uniform_op == TFHE_MUX;
 
     TimedLaunch tl{};
     if (ck->profile) if (int rc = begin_timed(ck, 0, stream, tl)) return rc;
     if (int rc = launch_blind_rotate(br, gates_per_group(), stream)) return rc;
     if (ck->profile) if (int rc = end_timed(ck, stream, tl)) return rc;
+    if (has_mux) if (int rc = launch_mux_combine(br.ext, d_recs, count, stream)) return rc;
     if (ck->profile) if (int rc = begin_timed(ck, 1, stream, tl)) return rc;
     if (int rc = launch_key_switch(ks, stream)) return rc;
     if (ck->profile) if (int rc = end_timed(ck, stream, tl)) return rc;
@@ -119,26 +123,46 @@ int run_gate_stream(tfhe_cloud_key *ck, const tfhe_gate_rec *gates, size_t ngate
     if (ngates == 0) return TFHE_OK;
     if (ngates > (size_t)INT32_MAX || nwires > (size_t)INT32_MAX)
         return set_error(TFHE_E_SIZE, "too many gates or wires");
-    // writer of each wire; an input must be produced by an earlier record or by nobody
+    // writer of each wire; an input must be produced by an earlier record or by nobody.  The
+    // second record of a multiplexer shares its output with the first and is not a writer.
     std::vector<int32_t> writer(nwires, -1);
     for (size_t g = 0; g < ngates; ++g) {
         const tfhe_gate_rec &r = gates[g];
-        if (r.op > TFHE_XNOR || r.neg0 > 1 || r.neg1 > 1)
+        if (r.op > TFHE_MUX_ELSE || r.neg0 > 1 || r.neg1 > 1)
             return set_error(TFHE_E_PARAM, "gate %zu: bad opcode or flag", g);
         if (r.in0 < 0 || r.in1 < 0 || r.out < 0 || (size_t)r.in0 >= nwires || (size_t)r.in1 >= nwires ||
             (size_t)r.out >= nwires)
             return set_error(TFHE_E_SIZE, "gate %zu: wire index out of range", g);
+        if (r.op == TFHE_MUX) {
+            if (g + 1 >= ngates || gates[g + 1].op != TFHE_MUX_ELSE || gates[g + 1].in0 != r.in0 ||
+                gates[g + 1].out != r.out || gates[g + 1].neg0 != r.neg0)
+                return set_error(TFHE_E_PARAM, "gate %zu: TFHE_MUX must be followed by its TFHE_MUX_ELSE "
+                                               "with the same selector, selector flag and output", g);
+        } else if (r.op == TFHE_MUX_ELSE) {
+            if (g == 0 || gates[g - 1].op != TFHE_MUX)
+                return set_error(TFHE_E_PARAM, "gate %zu: TFHE_MUX_ELSE without its TFHE_MUX", g);
+            continue;
+        }
         if (writer[r.out] >= 0) return set_error(TFHE_E_PARAM, "gate %zu: wire %d written twice", g, r.out);
         writer[r.out] = (int32_t)g;
     }
     std::vector<int32_t> level(ngates);
     std::vector<int32_t> depth(nwires, 0);
     int32_t max_level = 0;
+    bool any_mux = false;
     for (size_t g = 0; g < ngates; ++g) {
         const tfhe_gate_rec &r = gates[g];
-        if (writer[r.in0] >= (int32_t)g || writer[r.in1] >= (int32_t)g)
+        if (r.op == TFHE_MUX_ELSE) { level[g] = level[g - 1]; continue; }
+        const int32_t self = (int32_t)g;
+        if (writer[r.in0] >= self || writer[r.in1] >= self)
             return set_error(TFHE_E_PARAM, "gate %zu reads a wire written by itself or a later record", g);
-        const int32_t lv = 1 + std::max(depth[r.in0], depth[r.in1]);
+        int32_t lv = 1 + std::max(depth[r.in0], depth[r.in1]);
+        if (r.op == TFHE_MUX) {
+            any_mux = true;
+            if (writer[gates[g + 1].in1] >= self)
+                return set_error(TFHE_E_PARAM, "gate %zu reads a wire written by itself or a later record", g + 1);
+            lv = std::max(lv, 1 + depth[gates[g + 1].in1]);
+        }
         level[g] = lv;
         depth[r.out] = lv;
         max_level = std::max(max_level, lv);
@@ -161,9 +185,11 @@ int run_gate_stream(tfhe_cloud_key *ck, const tfhe_gate_rec *gates, size_t ngate
     TFHE_HIP(hipStreamSynchronize(stream));
     const tfhe_gate_rec *d_recs = (const tfhe_gate_rec *)ck->ws_gates.ptr;
     for (int32_t l = 1; l <= max_level; ++l) {
-        for (size_t at = start[l]; at < start[l + 1]; at += kChunkGates) {
-            const size_t cnt = std::min(kChunkGates, start[l + 1] - at);
-            if (int rc = run_batch(ck, d_recs + at, 0, wires, wires, wires, cnt, stream)) return rc;
+        for (size_t at = start[l]; at < start[l + 1];) {
+            size_t cnt = std::min(kChunkGates, start[l + 1] - at);
+            if (sorted[at + cnt - 1].op == TFHE_MUX) --cnt;      // keep the two halves in one batch
+            if (int rc = run_batch(ck, d_recs + at, 0, wires, wires, wires, wires, cnt, any_mux, stream)) return rc;
+            at += cnt;
         }
     }
     return TFHE_OK;
@@ -241,7 +267,8 @@ void tfhe_free_cloud_key(tfhe_cloud_key *ck) {
 int tfhe_gate_batch(tfhe_cloud_key *ck, int op, const uint32_t *a, const uint32_t *b, uint32_t *out,
                     size_t count, void *stream) {
     if (int rc = ensure_uploaded(ck)) return rc;
-    if (op < TFHE_NAND || op > TFHE_XNOR) return set_error(TFHE_E_PARAM, "unknown gate opcode %d", op);
+    if (op < TFHE_NAND || op > TFHE_XNOR)
+        return set_error(TFHE_E_PARAM, "unknown two-input gate opcode %d (multiplexers: tfhe_mux_batch)", op);
     if (count == 0) return TFHE_OK;
     if (!a || !b || !out) return set_error(TFHE_E_NULL, "NULL ciphertext buffer");
     const size_t words = (size_t)ck->params.n + 1;
@@ -249,8 +276,26 @@ int tfhe_gate_batch(tfhe_cloud_key *ck, int op, const uint32_t *a, const uint32_
     if (int rc = ck->ws_ext.reserve(biggest * (size_t)(ck->params.N + 1) * sizeof(uint32_t))) return rc;
     for (size_t at = 0; at < count; at += kChunkGates) {
         const size_t cnt = std::min(kChunkGates, count - at);
-        if (int rc = run_batch(ck, nullptr, op, a + at * words, b + at * words, out + at * words, cnt,
-                               (hipStream_t)stream))
+        if (int rc = run_batch(ck, nullptr, op, a + at * words, b + at * words, nullptr, out + at * words, cnt,
+                               false, (hipStream_t)stream))
+            return rc;
+    }
+    return TFHE_OK;
+}
+
+int tfhe_mux_batch(tfhe_cloud_key *ck, const uint32_t *s, const uint32_t *a, const uint32_t *b, uint32_t *out,
+                   size_t count, void *stream) {
+    if (int rc = ensure_uploaded(ck)) return rc;
+    if (count == 0) return TFHE_OK;
+    if (!s || !a || !b || !out) return set_error(TFHE_E_NULL, "NULL ciphertext buffer");
+    const size_t words = (size_t)ck->params.n + 1;
+    const size_t per_batch = kChunkGates / 2;          // two launch items per multiplexer
+    const size_t biggest = 2 * std::min(per_batch, count);
+    if (int rc = ck->ws_ext.reserve(biggest * (size_t)(ck->params.N + 1) * sizeof(uint32_t))) return rc;
+    for (size_t at = 0; at < count; at += per_batch) {
+        const size_t cnt = std::min(per_batch, count - at);
+        if (int rc = run_batch(ck, nullptr, TFHE_MUX, s + at * words, a + at * words, b + at * words,
+                               out + at * words, 2 * cnt, true, (hipStream_t)stream))
             return rc;
     }
     return TFHE_OK;

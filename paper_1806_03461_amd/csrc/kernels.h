@@ -8,6 +8,8 @@ struct BlindRotateArgs {
     const tfhe_gate_rec *recs;   // device; NULL: gate i reads in0[i], in1[i] with uniform_op
     int uniform_op;
     const uint32_t *in0, *in1;   // device wire arrays the records index into
+    const uint32_t *in1_alt;     // uniform TFHE_MUX only: launch item 2g is AND(in0[g], in1[g]),
+                                 // item 2g+1 is AND(NOT in0[g], in1_alt[g])
     uint32_t *ext;               // device [count][1025]: extracted samples
     size_t count;
     const double2 *bk_fft;       // device [n][4][4][512]
@@ -23,6 +25,7 @@ struct KeySwitchArgs {
     size_t count;
     const uint32_t *ksk;         // device [1024][t][2^basebit - 1][stride] plus one zero row
     int n, t, basebit;
+    int uniform_mux;             // recs == NULL: items come in pairs, item 2g carries the sum and writes out[g]
     int group;                   // gates sharing one pass over the key (1 = one gate per workgroup)
     int stride;                  // words per key row on the device: n+1 rounded up to even, pad = 0
 };
@@ -32,6 +35,8 @@ int launch_bk_to_spectrum(const uint32_t *bk_raw, double2 *bk_fft, const double2
                           hipStream_t stream);
 int launch_blind_rotate(const BlindRotateArgs &a, int gates_per_group, hipStream_t stream);
 int launch_key_switch(const KeySwitchArgs &a, hipStream_t stream);
+// ext[e] += ext[e+1]; ext[e].body += 1/8 for every first half e of a multiplexer
+int launch_mux_combine(uint32_t *ext, const tfhe_gate_rec *recs, size_t count, hipStream_t stream);
 int launch_gather_outputs(const uint32_t *wires, const tfhe_out_ref *refs, uint32_t *out, size_t count,
                           int words, hipStream_t stream);
 int launch_fill_trivial(uint32_t *ct, int words, int bit, hipStream_t stream);

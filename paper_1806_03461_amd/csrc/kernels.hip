@@ -162,18 +162,26 @@ __global__ __launch_bounds__(kThreadsPerGate *B) __attribute__((amdgpu_waves_per
         int op = a.uniform_op;
         size_t i0 = gi, i1 = gi;
         uint32_t s0 = 1u, s1 = 1u;
+        const uint32_t *src1 = a.in1;
         if (live && a.recs) {
             const tfhe_gate_rec r = a.recs[gi];
             op = r.op; i0 = (size_t)r.in0; i1 = (size_t)r.in1;
             s0 = r.neg0 ? 0xFFFFFFFFu : 1u; s1 = r.neg1 ? 0xFFFFFFFFu : 1u;
+        } else if (live && op == TFHE_MUX) {
+            i0 = i1 = gi >> 1;
+            if (gi & 1) { op = TFHE_MUX_ELSE; src1 = a.in1_alt; }
         }
+        // a multiplexer half is an AND whose result stays under the ring key:
+        // AND(s, a), then AND(NOT s, b)
+        if (op == TFHE_MUX_ELSE) s0 = 0u - s0;
+        if (op >= TFHE_MUX) op = TFHE_AND;
         uint32_t kappa, mult;
         gate_constants(op, kappa, mult);
         const size_t w = (size_t)a.n + 1;
         for (int j = lt; j <= a.n; j += kThreadsPerGate) {
             uint32_t c = 0;
             if (live) {
-                c = mult * (s0 * a.in0[i0 * w + j] + s1 * a.in1[i1 * w + j]);
+                c = mult * (s0 * a.in0[i0 * w + j] + s1 * src1[i1 * w + j]);
                 if (j == a.n) c += kappa;
             }
             my.bar[j] = (uint16_t)(((c + (1u << 20)) >> 21) & 2047u);
@@ -313,6 +321,8 @@ __global__ __launch_bounds__(256) void key_switch_kernel(KeySwitchArgs a) {
     __shared__ uint32_t ext[kN + 1];
     const int tid = threadIdx.x;
     const size_t gi = blockIdx.x;
+    // the second half of a multiplexer has been added into the first: nothing to switch
+    if (a.recs ? a.recs[gi].op == TFHE_MUX_ELSE : (a.uniform_mux && (gi & 1))) return;
     const uint32_t *src = a.ext + gi * (size_t)(kN + 1);
     for (int j = tid; j <= kN; j += 256) ext[j] = src[j];
     __syncthreads();
@@ -351,7 +361,7 @@ __global__ __launch_bounds__(256) void key_switch_kernel(KeySwitchArgs a) {
             }
         }
     }
-    const size_t out_index = a.recs ? (size_t)a.recs[gi].out : gi;
+    const size_t out_index = a.recs ? (size_t)a.recs[gi].out : (a.uniform_mux ? gi >> 1 : gi);
     uint32_t *out = a.out + out_index * (size_t)words;
 #pragma unroll
     for (int q = 0; q < kMaxPerThread; ++q) {
@@ -382,10 +392,15 @@ __global__ __launch_bounds__(256) void key_switch_shared_kernel(KeySwitchArgs a)
     const bool owner = 2 * tid < words;            // 2p+1 may be the zero padding word of a row
     const int pair = owner ? tid : 0;              // idle threads shadow pair 0 and store nothing
 
+    // an item is live if it exists and is not the second half of a multiplexer
+    auto is_live = [&](size_t gi) {
+        if (gi >= a.count) return false;
+        return a.recs ? a.recs[gi].op != TFHE_MUX_ELSE : !(a.uniform_mux && (gi & 1));
+    };
     uint2 acc[G];
 #pragma unroll
     for (int g = 0; g < G; ++g) {
-        const bool live = g0 + g < a.count;
+        const bool live = is_live(g0 + g);
         const uint32_t body = live ? a.ext[(g0 + g) * (size_t)(kN + 1) + kN] : 0u;
         acc[g].x = 2 * pair == a.n ? body : 0u;
         acc[g].y = 2 * pair + 1 == a.n ? body : 0u;
@@ -397,7 +412,7 @@ __global__ __launch_bounds__(256) void key_switch_shared_kernel(KeySwitchArgs a)
         __syncthreads();
         for (int idx = tid; idx < kChunk * G; idx += 256) {
             const int g = idx / kChunk, ii = idx % kChunk;
-            const bool live = g0 + g < a.count;
+            const bool live = is_live(g0 + g);
             mask_words[ii][g] = live ? a.ext[(g0 + g) * (size_t)(kN + 1) + i0 + ii] + round : 0u;
         }
         __syncthreads();
@@ -431,14 +446,26 @@ __global__ __launch_bounds__(256) void key_switch_shared_kernel(KeySwitchArgs a)
     if (owner) {
 #pragma unroll
         for (int g = 0; g < G; ++g) {
-            if (g0 + g < a.count) {
-                const size_t out_index = a.recs ? (size_t)a.recs[g0 + g].out : g0 + g;
+            if (is_live(g0 + g)) {
+                const size_t out_index =
+                    a.recs ? (size_t)a.recs[g0 + g].out : (a.uniform_mux ? (g0 + g) >> 1 : g0 + g);
                 uint32_t *out = a.out + out_index * (size_t)words;
                 out[2 * pair] = acc[g].x;
                 if (2 * pair + 1 < words) out[2 * pair + 1] = acc[g].y;
             }
         }
     }
+}
+
+// Multiplexer: the two half results (ring-key samples of AND(s,a) and AND(NOT s,b)) are summed,
+// 1/8 is added to the body, and the sum is what the key switch of the first half consumes.
+__global__ void mux_combine_kernel(uint32_t *ext, const tfhe_gate_rec *recs, size_t count) {
+    const size_t e = blockIdx.x;
+    const bool first = recs ? recs[e].op == TFHE_MUX : (e & 1) == 0;
+    if (!first || e + 1 >= count) return;
+    uint32_t *dst = ext + e * (size_t)(kN + 1);
+    const uint32_t *add = dst + (kN + 1);
+    for (int j = threadIdx.x; j <= kN; j += blockDim.x) dst[j] += add[j] + (j == kN ? kEighth : 0u);
 }
 
 // out[k] = +-wires[ref.wire]  or the noiseless sample of the constant bit
@@ -527,6 +554,13 @@ int launch_key_switch(const KeySwitchArgs &a, hipStream_t stream) {
 #undef KS_CASE
     default: return set_error(TFHE_E_PARAM, "unsupported key-switch digit count %d", a.t);
     }
+    TFHE_HIP(hipGetLastError());
+    return TFHE_OK;
+}
+
+int launch_mux_combine(uint32_t *ext, const tfhe_gate_rec *recs, size_t count, hipStream_t stream) {
+    if (count == 0) return TFHE_OK;
+    hipLaunchKernelGGL(mux_combine_kernel, dim3((unsigned)count), dim3(256), 0, stream, ext, recs, count);
     TFHE_HIP(hipGetLastError());
     return TFHE_OK;
 }

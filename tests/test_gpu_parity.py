@@ -210,3 +210,43 @@ def test_results_do_not_depend_on_batching(gpu):
     T.tfhe_profile_enable(ck, False)
     assert np.array_equal(T.to_host(wires[2 * cnt:]), first)
     assert prof["gates"] == cnt and prof["blind_rotate_launches"] == 1 and prof["blind_rotate_ms"] > 0
+
+
+def test_mux_gate_batch_and_stream(gpu, real_keys):
+    """The three-input multiplexer: all eight input combinations (plus a ragged tail) through
+    tfhe_mux_batch, and a small layer whose comparator is Algorithm 1's MUX chain, byte for byte
+    against the oracle."""
+    import torch
+    T, sk, ck = gpu
+    s = np.array([0, 0, 0, 0, 1, 1, 1, 1, 1, 0, 1], np.uint8)
+    a = np.array([0, 0, 1, 1, 0, 0, 1, 1, 0, 1, 1], np.uint8)
+    b = np.array([0, 1, 0, 1, 0, 1, 0, 1, 1, 0, 0], np.uint8)
+    cs, ca, cb = T.tfhe_encrypt(sk, 91, s), T.tfhe_encrypt(sk, 92, a), T.tfhe_encrypt(sk, 93, b)
+    out = torch.empty((len(s), 501), dtype=torch.int32, device="cuda")
+    T.tfhe_mux_batch(ck, T.to_device(cs), T.to_device(ca), T.to_device(cb), out, len(s))
+    torch.cuda.synchronize()
+    got = T.to_host(out)
+    assert list(T.tfhe_decrypt(sk, got)) == [int(x if c else y) for c, x, y in zip(s, a, b)]
+    want = np.stack([real_keys.mux(cs[i], ca[i], cb[i]) for i in range(len(s))])
+    assert np.array_equal(got, want)
+    # Algorithm 1 as printed, inside a layer
+    rng = np.random.default_rng(95)
+    d, p = 11, 3
+    W = rng.choice(np.array([-1, 0, 1], np.int8), (p, d), p=[0.45, 0.1, 0.45])
+    Tt = np.array([3, 6, 5], np.int32)
+    x = rng.integers(0, 2, d).astype(np.uint8)
+    ctx = T.tfhe_encrypt(sk, 96, x)
+    res = torch.empty((p, 501), dtype=torch.int32, device="cuda")
+    T.bnn_dense_encrypted_opts(ck, T.to_device(ctx), d, W, Tt, p, res, 0, T.LOWER_MUX_COMPARATOR)
+    torch.cuda.synchronize()
+    cir, o = cc.dense_layer(d, W, Tt, comparator="mux")
+    ref, _ = cc.eval_encrypted(real_keys, cir, ctx, o, threads=16)
+    assert np.array_equal(T.to_host(res), ref)
+    assert np.array_equal(T.tfhe_decrypt(sk, T.to_host(res)), cc.dense_plain(x, W, Tt))
+    # malformed pairs are refused
+    wires = torch.zeros((6, 501), dtype=torch.int32, device="cuda")
+    lone = np.array([(T.MUX, 0, 0, 0, 0, 1, 4)], dtype=T.GATE_DTYPE)
+    other_sel = np.array([(T.MUX, 0, 0, 0, 0, 1, 4), (T.MUX_ELSE, 0, 0, 0, 2, 3, 4)], dtype=T.GATE_DTYPE)
+    for bad in (lone, other_sel, other_sel[1:]):
+        with pytest.raises(T.TfheError):
+            T.tfhe_gate_stream(ck, bad, wires, 6)

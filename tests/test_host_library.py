@@ -74,10 +74,19 @@ def canonical(gates, outs, n_wires, n_inputs):
     ident = {}
     for w in range(n_inputs + 2):
         ident[w] = _INTERN.setdefault(("in", w), len(_INTERN))
+    pending = None
     for g in gates:                                     # topological order
         a = (ident[int(g["in0"])], int(g["neg0"]))
         b = (ident[int(g["in1"])], int(g["neg1"]))
-        key = (int(g["op"]),) + tuple(sorted((a, b)))
+        if int(g["op"]) == 6:                           # multiplexer: (selector, then) ...
+            pending = (a, b)
+            continue
+        if int(g["op"]) == 7:                           # ... (same selector, else): ordered triple
+            assert pending is not None and pending[0] == a
+            key = ("mux", a, pending[1], b)
+            pending = None
+        else:
+            key = (int(g["op"]),) + tuple(sorted((a, b)))
         ident[int(g["out"])] = _INTERN.setdefault(key, len(_INTERN))
     return [("const", int(v)) if w < 0 else (ident[int(w)], int(v)) for w, v in outs]
 
@@ -108,6 +117,21 @@ def test_dense_lowering_is_the_oracle_circuit(d, p, sparse, with_T):
     mine = canonical(gates, [(int(r["wire"]), int(r["value"])) for r in outs], nw, d)
     theirs = canonical(cir.gate_array(), oracle_outs(o), cir.n_wires, d)
     assert mine == theirs
+
+
+@pytest.mark.parametrize("d,p", [(6, 3), (40, 4), (144, 2)])
+def test_mux_comparator_lowering_is_the_oracle_circuit(d, p):
+    rng = np.random.default_rng(d)
+    W = rng.choice(np.array([-1, 0, 1], np.int8), (p, d), p=[0.4, 0.2, 0.4])
+    Tt = rng.integers(-1, d + 2, p).astype(np.int32)
+    gates, outs, nw = T.bnn_dense_lower_opts(d, W, Tt, p, 0, T.LOWER_MUX_COMPARATOR)
+    cir, o = cc.dense_layer(d, W, Tt, comparator="mux")
+    assert nw == cir.n_wires and len(gates) == len(cir.gates)
+    mine = canonical(gates, [(int(r["wire"]), int(r["value"])) for r in outs], nw, d)
+    assert mine == canonical(cir.gate_array(), oracle_outs(o), cir.n_wires, d)
+    assert (gates["op"] == T.MUX).sum() == (gates["op"] == T.MUX_ELSE).sum() > 0
+    with pytest.raises(T.TfheError):
+        T.bnn_dense_lower_opts(d, W, Tt, p, 0, 8)
 
 
 def test_conv_lowering_is_the_oracle_circuit():
