@@ -35,6 +35,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="cfg3", choices=["cfg3", "cfg2", "flat"])
     ap.add_argument("--flat-count", type=int, default=65536)
+    ap.add_argument("--comparator", default="folded", choices=["folded", "mux"],
+                    help="threshold circuit: AND/OR chain folded by the plaintext bits (default) or "
+                         "Algorithm 1 as printed, one MUX gate per popcount bit")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--cpu-gates", type=int, default=512, help="gates in the oracle sample")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
@@ -70,11 +73,15 @@ def main():
         p, d = c["W"].shape
         x = T.to_device(T.tfhe_encrypt(sk, c["enc_seed"], c["x"]))
         out = torch.empty((p, words), dtype=torch.int32, device="cuda")
-        gates_host, _, _ = T.bnn_dense_lower(d, c["W"], c["T"], p)
-        gates_per_step = len(gates_host)
+        flags = T.LOWER_MUX_COMPARATOR if args.comparator == "mux" else T.LOWER_DEFAULT
+        gates_host, _, _ = T.bnn_dense_lower_opts(d, c["W"], c["T"], p, 0, flags)
+        # a multiplexer is two records (two blind rotations) but one gate
+        gates_per_step = int((gates_host["op"] != T.MUX_ELSE).sum())
+        if args.comparator == "mux":
+            name += ", Algorithm-1 MUX comparator"
 
         def step():
-            T.bnn_dense_encrypted(ck, x, d, c["W"], c["T"], p, out)
+            T.bnn_dense_encrypted_opts(ck, x, d, c["W"], c["T"], p, out, 0, flags)
     else:
         rng = np.random.default_rng(0)
         cnt = args.flat_count
@@ -125,7 +132,7 @@ def main():
     # average launch duration, from HIP events recorded around every launch on the call's stream
     br_launches = max(1, prof["blind_rotate_launches"])
     br_avg_ms = prof["blind_rotate_ms"] / br_launches
-    gates_per_launch = prof["gates"] / br_launches
+    gates_per_launch = prof["gates"] / br_launches          # blind rotations per launch
     flops_per_gate = FLOPS_PER_STEP * P.n
     achieved = flops_per_gate * gates_per_launch / (br_avg_ms * 1e-3) / 1e12 if br_avg_ms > 0 else 0.0
     # HBM bytes per launch of that kernel, from the committed rocprofv3 counter summary (if one

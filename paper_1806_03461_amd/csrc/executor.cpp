@@ -101,6 +101,15 @@ int run_batch(tfhe_cloud_key *ck, const tfhe_gate_rec *d_recs, int uniform_op, c
     ks.ext = br.ext; ks.recs = d_recs; ks.out = out; ks.count = count; ks.ksk = ck->d_ksk;
     ks.n = P.n; ks.t = P.ks_t; ks.basebit = P.ks_basebit; ks.stride = (P.n + 2) & ~1;
     ks.group = key_switch_group(count);
+    // few gates (the deep, narrow levels of a circuit): spread each gate over several
+    // workgroups so that the whole chip works on the batch
+    ks.splits = 1;
+    if (ks.group == 1) {
+        static int forced = -1;
+        if (forced < 0) { const char *e = getenv("TFHE_KS_SPLITS"); forced = e ? atoi(e) : 0; }
+        if (forced > 0) ks.splits = forced;
+        else while (ks.splits < 16 && count * ks.splits < 4096) ks.splits *= 2;
+    }
     ks.uniform_mux = !d_recs && uniform_op == TFHE_MUX;
 
     TimedLaunch tl{};

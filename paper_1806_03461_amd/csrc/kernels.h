@@ -26,6 +26,7 @@ struct KeySwitchArgs {
     const uint32_t *ksk;         // device [1024][t][2^basebit - 1][stride] plus one zero row
     int n, t, basebit;
     int uniform_mux;             // recs == NULL: items come in pairs, item 2g carries the sum and writes out[g]
+    int splits;                  // group == 1 only: workgroups sharing one gate's mask words (power of two)
     int group;                   // gates sharing one pass over the key (1 = one gate per workgroup)
     int stride;                  // words per key row on the device: n+1 rounded up to even, pad = 0
 };

@@ -320,7 +320,10 @@ template <int T>
 __global__ __launch_bounds__(256) void key_switch_kernel(KeySwitchArgs a) {
     __shared__ uint32_t ext[kN + 1];
     const int tid = threadIdx.x;
-    const size_t gi = blockIdx.x;
+    // with a.splits > 1 the mask words of one gate are shared out over that many workgroups,
+    // each adding its partial result into the (zeroed) output with integer atomics
+    const size_t gi = blockIdx.x / a.splits;
+    const int part = (int)(blockIdx.x % a.splits);
     // the second half of a multiplexer has been added into the first: nothing to switch
     if (a.recs ? a.recs[gi].op == TFHE_MUX_ELSE : (a.uniform_mux && (gi & 1))) return;
     const uint32_t *src = a.ext + gi * (size_t)(kN + 1);
@@ -333,13 +336,14 @@ __global__ __launch_bounds__(256) void key_switch_kernel(KeySwitchArgs a) {
 #pragma unroll
     for (int q = 0; q < kMaxPerThread; ++q) {
         const int w = tid + 256 * q;
-        acc[q] = w == a.n ? ext[kN] : 0u;
+        acc[q] = (w == a.n && part == 0) ? ext[kN] : 0u;
     }
     const int values = (1 << a.basebit) - 1;
     const uint32_t round = 1u << (31 - T * a.basebit);
     const size_t zero_row = (size_t)kN * T * values;   // appended row of zeros
     const int per_thread = (words + 255) >> 8;
-    for (int i = 0; i < kN; ++i) {
+    const int i_begin = part * (kN / a.splits), i_end = i_begin + kN / a.splits;
+    for (int i = i_begin; i < i_end; ++i) {
         const uint32_t ai = ext[i] + round;
         const uint32_t *rows[T];
 #pragma unroll
@@ -351,12 +355,12 @@ __global__ __launch_bounds__(256) void key_switch_kernel(KeySwitchArgs a) {
         for (int q = 0; q < per_thread; ++q) {
             const int w = tid + 256 * q;
             if (w < words) {
-                uint32_t part[T];
+                uint32_t part_sum[T];
 #pragma unroll
-                for (int j = 0; j < T; ++j) part[j] = rows[j][w];
+                for (int j = 0; j < T; ++j) part_sum[j] = rows[j][w];
                 uint32_t sum = 0;
 #pragma unroll
-                for (int j = 0; j < T; ++j) sum += part[j];
+                for (int j = 0; j < T; ++j) sum += part_sum[j];
                 acc[q] -= sum;
             }
         }
@@ -366,8 +370,20 @@ __global__ __launch_bounds__(256) void key_switch_kernel(KeySwitchArgs a) {
 #pragma unroll
     for (int q = 0; q < kMaxPerThread; ++q) {
         const int w = tid + 256 * q;
-        if (w < words) out[w] = acc[q];
+        if (w < words) {
+            if (a.splits > 1) atomicAdd(out + w, acc[q]);
+            else out[w] = acc[q];
+        }
     }
+}
+
+// zero the output samples that the split key switch accumulates into
+__global__ void zero_outputs_kernel(KeySwitchArgs a) {
+    const size_t gi = blockIdx.x;
+    if (a.recs ? a.recs[gi].op == TFHE_MUX_ELSE : (a.uniform_mux && (gi & 1))) return;
+    const size_t out_index = a.recs ? (size_t)a.recs[gi].out : (a.uniform_mux ? gi >> 1 : gi);
+    uint32_t *out = a.out + out_index * (size_t)(a.n + 1);
+    for (int w = threadIdx.x; w <= a.n; w += blockDim.x) out[w] = 0u;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -546,7 +562,13 @@ int launch_key_switch(const KeySwitchArgs &a, hipStream_t stream) {
         TFHE_HIP(hipGetLastError());
         return TFHE_OK;
     }
-    const dim3 grid((unsigned)a.count), block(256);
+    if (a.splits < 1 || (a.splits & (a.splits - 1)) || a.splits > 64)
+        return set_error(TFHE_E_PARAM, "key-switch splits must be a power of two <= 64");
+    if (a.splits > 1) {
+        hipLaunchKernelGGL(zero_outputs_kernel, dim3((unsigned)a.count), dim3(256), 0, stream, a);
+        TFHE_HIP(hipGetLastError());
+    }
+    const dim3 grid((unsigned)(a.count * a.splits)), block(256);
     switch (a.t) {
 #define KS_CASE(T) case T: hipLaunchKernelGGL(key_switch_kernel<T>, grid, block, 0, stream, a); break;
         KS_CASE(1) KS_CASE(2) KS_CASE(3) KS_CASE(4) KS_CASE(5) KS_CASE(6) KS_CASE(7) KS_CASE(8)
