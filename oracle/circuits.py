@@ -141,6 +141,44 @@ def threshold_chain_mux(cir, number, T):
     return o
 
 
+def complement(number):
+    """2^w - 1 - S for a w-bit encrypted number: negate every bit (no gate)."""
+    bits, _ = number
+    return ([(w, n ^ 1) for (w, n) in bits], (1 << len(bits)) - 1)
+
+
+def neuron_plus_one(cir, x_literals, w_row, T, X):
+    """The '+1' trick (Sec. 4.2): sum only the inputs of the rarer weight sign and use the
+    popcount X of all inputs, shared by every unit reading the same inputs.  With
+    P = sum of x over w=+1, Q = sum over w=-1, X = P + Q and the agreements S = P + |neg| - Q:
+        S >= T  <=>  2P - X >= c  <=>  X - 2Q >= c,      c = T - |neg|.
+    The subtraction is an addition of the bitwise complement (negated ciphertexts, free):
+        |pos| <= |neg|:  U = 2P + ~X,   test U >= c + (2^wx - 1);
+        otherwise:       U = X + 2(~Q), test U >= c + 2 (2^wq - 1).
+    The factor 2 is a shift: bit 0 of U is bit 0 of the unshifted operand, the rest is one
+    ripple-carry addition.  Weights must be +-1 (a zero weight would change X per unit)."""
+    pos = [lit for lit, w in zip(x_literals, w_row) if w > 0]
+    neg = [lit for lit, w in zip(x_literals, w_row) if w < 0]
+    assert len(pos) + len(neg) == len(x_literals), "the +1 trick needs weights in {-1,+1}"
+    c = int(T) - len(neg)
+    if len(pos) <= len(neg):
+        small = popcount_tree(cir, pos)                    # P
+        other = complement(X)                              # ~X
+        offset = other[1]
+    else:
+        small = complement(popcount_tree(cir, neg))        # ~Q
+        other = X
+        offset = 2 * small[1]
+    low = other[0][0]
+    high = (other[0][1:], other[1] >> 1)
+    if small[0] and high[0]:
+        total = add_numbers(cir, small, high)
+    else:
+        total = small if small[0] else high
+    U = ([low] + total[0], 2 * total[1] + 1)
+    return [threshold_chain(cir, U, c + offset)]
+
+
 def neuron(cir, x_literals, w_row, T, out_bits=0, comparator="folded"):
     """One output unit.  x_literals[i] is the literal of input i; w in {-1,0,+1}.
     Returns one literal/constant (T given) or out_bits popcount literals (T None)."""
@@ -160,13 +198,20 @@ def neuron(cir, x_literals, w_row, T, out_bits=0, comparator="folded"):
     return bits
 
 
-def dense_layer(d, W, T, out_bits=0, comparator="folded"):
-    """Circuit of a fully connected layer.  Returns (circuit, outputs)."""
+def dense_layer(d, W, T, out_bits=0, comparator="folded", plus_one=False):
+    """Circuit of a fully connected layer.  Returns (circuit, outputs).  With plus_one the rows
+    without zero weights use the '+1' trick on one shared popcount of the inputs."""
     cir = Circuit(d)
     x = [(i, 0) for i in range(d)]
     outs = []
+    X = None
     for j in range(W.shape[0]):
-        outs += neuron(cir, x, W[j], None if T is None else T[j], out_bits, comparator)
+        if plus_one and T is not None and d > 1 and (W[j] != 0).all():
+            if X is None:
+                X = popcount_tree(cir, x)
+            outs += neuron_plus_one(cir, x, W[j], T[j], X)
+        else:
+            outs += neuron(cir, x, W[j], None if T is None else T[j], out_bits, comparator)
     return cir, outs
 
 
@@ -185,8 +230,9 @@ def conv_pixel_literals(cir, C_, H, Wd, kh, kw, stride, pad, y, x):
     return lits
 
 
-def conv_layer(C_, H, Wd, K, T, stride, pad, pixels=None):
-    """Circuit of a convolution layer (or of the listed output pixels (o, y, x) only)."""
+def conv_layer(C_, H, Wd, K, T, stride, pad, pixels=None, plus_one=False):
+    """Circuit of a convolution layer (or of the listed output pixels (o, y, x) only).  With
+    plus_one the popcount of a receptive field is shared by the output channels of its pixel."""
     O, _, kh, kw = K.shape
     Ho = (H + 2 * pad - kh) // stride + 1
     Wo = (Wd + 2 * pad - kw) // stride + 1
@@ -194,9 +240,16 @@ def conv_layer(C_, H, Wd, K, T, stride, pad, pixels=None):
     if pixels is None:
         pixels = [(o, y, x) for o in range(O) for y in range(Ho) for x in range(Wo)]
     outs = []
+    field_sum = {}
     for (o, y, x) in pixels:
         lits = conv_pixel_literals(cir, C_, H, Wd, kh, kw, stride, pad, y, x)
-        outs += neuron(cir, lits, K[o].reshape(-1), T[o])
+        w = K[o].reshape(-1)
+        if plus_one and len(lits) > 1 and (w != 0).all():
+            if (y, x) not in field_sum:
+                field_sum[(y, x)] = popcount_tree(cir, lits)
+            outs += neuron_plus_one(cir, lits, w, T[o], field_sum[(y, x)])
+        else:
+            outs += neuron(cir, lits, w, T[o])
     return cir, outs
 
 

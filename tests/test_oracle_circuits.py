@@ -242,3 +242,74 @@ def test_mux_comparator_encrypted_toy(orc, toy_keys):
     folded, fo = cc.dense_layer(d, W, T)
     ref, _ = cc.eval_encrypted(toy_keys, folded, ct, fo, threads=4)
     assert np.array_equal(toy_keys.decrypt(ref), toy_keys.decrypt(res))
+
+
+# --------------------------------------------------------------------------- the "+1" trick
+def test_plus_one_identity_of_the_paper():
+    """w.x = (1+w).(1+x) - sum(w) - (1+x).1 and (1+w).(1+x) = 4 * sum of x-bar over w=+1 (Sec. 4.2)."""
+    rng = np.random.default_rng(1)
+    for _ in range(200):
+        d = int(rng.integers(1, 60))
+        w = 2 * rng.integers(0, 2, d) - 1
+        xb = rng.integers(0, 2, d)
+        x = 2 * xb - 1
+        assert (w * x).sum() == ((1 + w) * (1 + x)).sum() - w.sum() - (1 + x).sum()
+        assert ((1 + w) * (1 + x)).sum() == 4 * xb[w == 1].sum()
+
+
+@pytest.mark.parametrize("d", [2, 3, 4, 5, 7, 8, 9])
+def test_plus_one_unit_exhaustive(d):
+    rng = np.random.default_rng(d)
+    rows = [np.ones(d, np.int8), -np.ones(d, np.int8)] + [(2 * rng.integers(0, 2, d) - 1).astype(np.int8) for _ in range(4)]
+    for w in rows:
+        for T in range(-1, d + 3):
+            cir, outs = cc.dense_layer(d, w.reshape(1, d), np.array([T]), plus_one=True)
+            for bits in itertools.product((0, 1), repeat=d):
+                x = np.array(bits, np.uint8)
+                assert cc.eval_plain(cir, x, outs)[0] == cc.dense_plain(x, w.reshape(1, d), np.array([T]))[0], (w, T, bits)
+
+
+@pytest.mark.parametrize("d,p", [(33, 6), (144, 4), (256, 3), (784, 3)])
+def test_plus_one_layer_random_and_gate_savings(d, p):
+    rng = np.random.default_rng(d)
+    W = (2 * rng.integers(0, 2, (p, d)) - 1).astype(np.int8)
+    T = rng.integers(d // 3, 2 * d // 3, p).astype(np.int32)
+    plain_cir, plain_outs = cc.dense_layer(d, W, T)
+    cir, outs = cc.dense_layer(d, W, T, plus_one=True)
+    for _ in range(6):
+        x = rng.integers(0, 2, d).astype(np.uint8)
+        assert np.array_equal(cc.eval_plain(cir, x, outs), cc.dense_plain(x, W, T))
+    # per unit about half the gates; the shared popcount of the inputs is paid once per layer
+    shared = len(popcount_bits(d)[0].gates)
+    per_unit = (len(cir.gates) - shared) / p
+    assert per_unit < 0.62 * len(plain_cir.gates) / p
+    # a row with a dropped input falls back to the plain unit
+    W[0, 0] = 0
+    cir2, outs2 = cc.dense_layer(d, W, T, plus_one=True)
+    x = rng.integers(0, 2, d).astype(np.uint8)
+    assert np.array_equal(cc.eval_plain(cir2, x, outs2), cc.dense_plain(x, W, T))
+
+
+def test_plus_one_convolution():
+    rng = np.random.default_rng(5)
+    C_, H, Wd, O = 2, 4, 5, 3
+    x = rng.integers(0, 2, (C_, H, Wd)).astype(np.uint8)
+    K = (2 * rng.integers(0, 2, (O, C_, 3, 3)) - 1).astype(np.int8)
+    T = rng.integers(6, 13, O).astype(np.int32)
+    cir, outs = cc.conv_layer(C_, H, Wd, K, T, 1, 1, plus_one=True)
+    got = cc.eval_plain(cir, x.reshape(-1), outs).reshape(O, H, Wd)
+    assert np.array_equal(got, cc.conv_plain(x, K, T, 1, 1))
+    # only 3 channels share each receptive-field popcount here; still fewer gates than the plain units
+    assert len(cir.gates) < len(cc.conv_layer(C_, H, Wd, K, T, 1, 1)[0].gates)
+
+
+def test_plus_one_encrypted_toy(orc, toy_keys):
+    rng = np.random.default_rng(23)
+    d, p = 6, 3
+    W = (2 * rng.integers(0, 2, (p, d)) - 1).astype(np.int8)
+    T = np.array([2, 3, 4], np.int32)
+    x = rng.integers(0, 2, d).astype(np.uint8)
+    ct = toy_keys.encrypt(x, 8)
+    cir, outs = cc.dense_layer(d, W, T, plus_one=True)
+    res, _ = cc.eval_encrypted(toy_keys, cir, ct, outs, threads=4)
+    assert np.array_equal(toy_keys.decrypt(res), cc.dense_plain(x, W, T))
