@@ -38,6 +38,8 @@ def main():
     ap.add_argument("--comparator", default="folded", choices=["folded", "mux"],
                     help="threshold circuit: AND/OR chain folded by the plaintext bits (default) or "
                          "Algorithm 1 as printed, one MUX gate per popcount bit")
+    ap.add_argument("--plus-one", action="store_true",
+                    help="lower the layer with the '+1' trick (half-size trees on one shared input popcount)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--cpu-gates", type=int, default=512, help="gates in the oracle sample")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
@@ -74,6 +76,9 @@ def main():
         x = T.to_device(T.tfhe_encrypt(sk, c["enc_seed"], c["x"]))
         out = torch.empty((p, words), dtype=torch.int32, device="cuda")
         flags = T.LOWER_MUX_COMPARATOR if args.comparator == "mux" else T.LOWER_DEFAULT
+        if args.plus_one:
+            flags |= T.LOWER_PLUS_ONE
+            name += ", '+1' trick"
         gates_host, _, _ = T.bnn_dense_lower_opts(d, c["W"], c["T"], p, 0, flags)
         # a multiplexer is two records (two blind rotations) but one gate
         gates_per_step = int((gates_host["op"] != T.MUX_ELSE).sum())

@@ -174,7 +174,15 @@ enum { TFHE_LOWER_DEFAULT = 0,
        /* comparator exactly as Algorithm 1 prints it: one MUX gate per bit of S with noiseless
         * constants as data inputs (started from o = 1, see bnn_dense_lower), instead of the chain
         * folded to AND / OR gates by the plaintext threshold bits */
-       TFHE_LOWER_MUX_COMPARATOR = 1 };
+       TFHE_LOWER_MUX_COMPARATOR = 1,
+       /* the "+1" trick of Sec. 4.2: a unit whose weights are all +-1 sums only the inputs of its
+        * rarer weight sign (P over w = +1, or Q over w = -1) and uses the popcount X of all its
+        * inputs, computed once and shared by every unit reading the same inputs (a layer's units;
+        * a pixel's output channels):  S >= T  <=>  2P - X >= T - |neg|  <=>  X - 2Q >= T - |neg|.
+        * The subtraction is an addition of the negated (complemented) bits, the factor 2 a shift,
+        * so each unit costs a half-size tree, one ripple-carry adder and the threshold chain.
+        * Units with a zero weight are lowered the default way. */
+       TFHE_LOWER_PLUS_ONE = 2 };
 int bnn_dense_lower_opts(int d, const int8_t *W, const int32_t *T, int p, int out_bits, uint32_t flags,
                          tfhe_gate_rec **gates, size_t *ngates, tfhe_out_ref **outs, size_t *nouts,
                          size_t *nwires);
@@ -189,6 +197,13 @@ int bnn_dense_encrypted_opts(tfhe_cloud_key *ck, const uint32_t *x, int d, const
 int bnn_conv_lower(int C, int H, int Wd, const int8_t *K, int O, int kh, int kw, int stride,
                    int pad, const int32_t *T, tfhe_gate_rec **gates, size_t *ngates,
                    tfhe_out_ref **outs, size_t *nouts, size_t *nwires);
+
+int bnn_conv_lower_opts(int C, int H, int Wd, const int8_t *K, int O, int kh, int kw, int stride,
+                        int pad, const int32_t *T, uint32_t flags, tfhe_gate_rec **gates, size_t *ngates,
+                        tfhe_out_ref **outs, size_t *nouts, size_t *nwires);
+int bnn_conv_encrypted_opts(tfhe_cloud_key *ck, const uint32_t *x, int C, int H, int Wd,
+                            const int8_t *K, int O, int kh, int kw, int stride, int pad,
+                            const int32_t *T, uint32_t *out, uint32_t flags, void *stream);
 
 /* Evaluate a fully connected layer on ciphertexts.  x: DEVICE [d][n+1]; W, T as above (HOST);
  * out: DEVICE [p][n+1] (T given) or [p*out_bits][n+1] (T == NULL). */

@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(HERE, "libtfhe_mi355x.so")
 
 NAND, AND, OR, NOR, XOR, XNOR, MUX, MUX_ELSE = range(8)
 OPS = {"NAND": NAND, "AND": AND, "OR": OR, "NOR": NOR, "XOR": XOR, "XNOR": XNOR}
-LOWER_DEFAULT, LOWER_MUX_COMPARATOR = 0, 1
+LOWER_DEFAULT, LOWER_MUX_COMPARATOR, LOWER_PLUS_ONE = 0, 1, 2
 KEY_LWE_SK, KEY_TRLWE_SK, KEY_BK_RAW, KEY_KSK_RAW = range(4)
 
 GATE_DTYPE = np.dtype([("op", "u1"), ("neg0", "u1"), ("neg1", "u1"), ("pad", "u1"),
@@ -45,7 +45,7 @@ EXPORTS = ["tfhe_last_error", "tfhe_default_params", "tfhe_keygen", "tfhe_encryp
            "tfhe_trivial", "tfhe_export_key", "tfhe_get_params", "tfhe_free_secret_key",
            "tfhe_free_cloud_key", "tfhe_free_buffer", "tfhe_cloud_key_upload", "tfhe_gate_batch",
            "tfhe_mux_batch", "tfhe_gate_stream", "bnn_dense_lower", "bnn_dense_lower_opts", "bnn_conv_lower",
-           "bnn_dense_encrypted", "bnn_dense_encrypted_opts",
+           "bnn_conv_lower_opts", "bnn_dense_encrypted", "bnn_dense_encrypted_opts", "bnn_conv_encrypted_opts",
            "bnn_conv_encrypted", "tfhe_profile_enable", "tfhe_profile_read",
            "tfhe_rounding_margin_enable", "tfhe_rounding_margin_read"]
 
@@ -83,6 +83,9 @@ def lib():
         L.bnn_dense_lower.argtypes = [i32, vp, vp, i32, i32] + lower_tail
         L.bnn_dense_lower_opts.argtypes = [i32, vp, vp, i32, i32, C.c_uint32] + lower_tail
         L.bnn_dense_encrypted_opts.argtypes = [vp, vp, i32, vp, vp, i32, vp, i32, C.c_uint32, vp]
+        L.bnn_conv_lower_opts.argtypes = [i32, i32, i32, vp, i32, i32, i32, i32, i32, vp, C.c_uint32] + lower_tail
+        L.bnn_conv_encrypted_opts.argtypes = [vp, vp, i32, i32, i32, vp, i32, i32, i32, i32, i32, vp, vp,
+                                              C.c_uint32, vp]
         L.bnn_conv_lower.argtypes = [i32, i32, i32, vp, i32, i32, i32, i32, i32, vp] + lower_tail
         L.bnn_dense_encrypted.argtypes = [vp, vp, i32, vp, vp, i32, vp, i32, vp]
         L.bnn_conv_encrypted.argtypes = [vp, vp, i32, i32, i32, vp, i32, i32, i32, i32, i32, vp, vp, vp]
@@ -247,6 +250,25 @@ def bnn_conv_lower(C_, H, Wd, K, T, stride, pad):
     _check(lib().bnn_conv_lower(C_, H, Wd, K.ctypes.data, O, kh, kw, stride, pad, T.ctypes.data,
                                 C.byref(g), C.byref(ng), C.byref(o), C.byref(no), C.byref(nw)))
     return _take(g, ng, GATE_DTYPE), _take(o, no, OUT_DTYPE), nw.value
+
+
+def bnn_conv_lower_opts(C_, H, Wd, K, T, stride, pad, flags=0):
+    K = _host(K, np.int8)
+    T = _host(T, np.int32)
+    O, _, kh, kw = K.shape
+    g, o = C.c_void_p(), C.c_void_p()
+    ng, no, nw = C.c_size_t(), C.c_size_t(), C.c_size_t()
+    _check(lib().bnn_conv_lower_opts(C_, H, Wd, K.ctypes.data, O, kh, kw, stride, pad, T.ctypes.data, flags,
+                                     C.byref(g), C.byref(ng), C.byref(o), C.byref(no), C.byref(nw)))
+    return _take(g, ng, GATE_DTYPE), _take(o, no, OUT_DTYPE), nw.value
+
+
+def bnn_conv_encrypted_opts(ck, x, C_, H, Wd, K, T, stride, pad, out, flags=0, stream=None):
+    K = _host(K, np.int8)
+    T = _host(T, np.int32)
+    O, _, kh, kw = K.shape
+    _check(lib().bnn_conv_encrypted_opts(ck.handle, _dev_ptr(x), C_, H, Wd, K.ctypes.data, O, kh, kw, stride,
+                                         pad, T.ctypes.data, _dev_ptr(out), flags, _stream(stream)))
 
 
 def bnn_dense_encrypted(ck, x, d, W, T, p, out, out_bits=0, stream=None):

@@ -148,6 +148,47 @@ public:
         return o;
     }
 
+    // 2^w - 1 - S: every bit negated, no gate
+    static Number complement(const Number &S) {
+        Number c;
+        c.bits = S.bits;
+        for (Sig &b : c.bits) b.flag ^= 1;
+        c.bound = ((int64_t)1 << S.bits.size()) - 1;
+        return c;
+    }
+
+    // The "+1" trick: [S >= T] from a tree over the rarer weight sign and the shared popcount X
+    // of all inputs.  2P - X >= c  <=>  2P + ~X >= c + (2^wx - 1);  X - 2Q >= c  <=>
+    // X + 2(~Q) >= c + 2(2^wq - 1);  c = T - |neg|.  Bit 0 of the sum is bit 0 of the unshifted
+    // operand, the rest is one ripple-carry addition.
+    Sig at_least_plus_one(const std::vector<Sig> &inputs, const int8_t *w, int64_t T, const Number &X) {
+        std::vector<Sig> pos, neg;
+        for (size_t i = 0; i < inputs.size(); ++i) (w[i] > 0 ? pos : neg).push_back(inputs[i]);
+        const int64_t c = T - (int64_t)neg.size();
+        Number small, other;
+        int64_t offset;
+        if (pos.size() <= neg.size()) {
+            small = popcount(pos);
+            other = complement(X);
+            offset = other.bound;
+        } else {
+            small = complement(popcount(neg));
+            other = X;
+            offset = 2 * small.bound;
+        }
+        Number high;
+        high.bits.assign(other.bits.begin() + 1, other.bits.end());
+        high.bound = other.bound >> 1;
+        Number total;
+        if (!small.bits.empty() && !high.bits.empty()) total = add(small, high);
+        else total = small.bits.empty() ? high : small;
+        Number U;
+        U.bits.push_back(other.bits[0]);
+        U.bits.insert(U.bits.end(), total.bits.begin(), total.bits.end());
+        U.bound = 2 * total.bound + 1;
+        return at_least(U, c + offset);
+    }
+
     // one output unit over the listed inputs
     void unit(const std::vector<Sig> &inputs, const int8_t *w, const int32_t *T, int out_bits,
               std::vector<tfhe_out_ref> &outs, uint32_t flags = 0) {
@@ -193,7 +234,8 @@ int check_weights(const int8_t *W, size_t count) {
 
 int lower_dense(int d, const int8_t *W, const int32_t *T, int p, int out_bits, uint32_t flags, Builder &b,
                 std::vector<tfhe_out_ref> &outs) {
-    if (flags & ~(uint32_t)TFHE_LOWER_MUX_COMPARATOR) return set_error(TFHE_E_PARAM, "unknown lowering flags %u", flags);
+    if (flags & ~(uint32_t)(TFHE_LOWER_MUX_COMPARATOR | TFHE_LOWER_PLUS_ONE))
+        return set_error(TFHE_E_PARAM, "unknown lowering flags %u", flags);
     if (d < 1 || p < 1) return set_error(TFHE_E_SIZE, "layer sizes must be positive");
     if (!W) return set_error(TFHE_E_NULL, "W is NULL");
     if (!T) {
@@ -210,12 +252,24 @@ int lower_dense(int d, const int8_t *W, const int32_t *T, int p, int out_bits, u
     if (int rc = check_weights(W, (size_t)d * p)) return rc;
     std::vector<Sig> x(d);
     for (int i = 0; i < d; ++i) x[i] = Sig::of(i);
-    for (int j = 0; j < p; ++j) b.unit(x, W + (size_t)j * d, T ? T + j : nullptr, out_bits, outs, flags);
+    Number X;          // popcount of all inputs, built on first use, shared by the layer's units
+    for (int j = 0; j < p; ++j) {
+        const int8_t *w = W + (size_t)j * d;
+        const bool dense_row = std::all_of(w, w + d, [](int8_t v) { return v != 0; });
+        if ((flags & TFHE_LOWER_PLUS_ONE) && T && d > 1 && dense_row) {
+            if (X.bits.empty()) X = b.popcount(x);
+            const Sig o = b.at_least_plus_one(x, w, T[j], X);
+            outs.push_back(tfhe_out_ref{o.wire, o.flag});
+        } else {
+            b.unit(x, w, T ? T + j : nullptr, out_bits, outs, flags);
+        }
+    }
     return TFHE_OK;
 }
 
 int lower_conv(int C, int H, int Wd, const int8_t *K, int O, int kh, int kw, int stride, int pad,
-               const int32_t *T, Builder &b, std::vector<tfhe_out_ref> &outs) {
+               const int32_t *T, uint32_t flags, Builder &b, std::vector<tfhe_out_ref> &outs) {
+    if (flags & ~(uint32_t)TFHE_LOWER_PLUS_ONE) return set_error(TFHE_E_PARAM, "unknown lowering flags %u", flags);
     if (C < 1 || H < 1 || Wd < 1 || O < 1 || kh < 1 || kw < 1 || stride < 1 || pad < 0)
         return set_error(TFHE_E_SIZE, "bad convolution shape");
     if (!K || !T) return set_error(TFHE_E_NULL, "K or T is NULL");
@@ -224,6 +278,8 @@ int lower_conv(int C, int H, int Wd, const int8_t *K, int O, int kh, int kw, int
     if (int rc = check_weights(K, taps * O)) return rc;
     const int Ho = (H + 2 * pad - kh) / stride + 1, Wo = (Wd + 2 * pad - kw) / stride + 1;
     std::vector<Sig> field(taps);
+    // "+1" trick: the popcount of a pixel's receptive field is shared by its output channels
+    std::vector<Number> field_sum((flags & TFHE_LOWER_PLUS_ONE) ? (size_t)Ho * Wo : 0);
     for (int o = 0; o < O; ++o)
         for (int y = 0; y < Ho; ++y)
             for (int x = 0; x < Wo; ++x) {
@@ -235,7 +291,16 @@ int lower_conv(int C, int H, int Wd, const int8_t *K, int O, int kh, int kw, int
                             const bool inside = iy >= 0 && iy < H && ix >= 0 && ix < Wd;
                             field[t] = Sig::of(inside ? (c * H + iy) * Wd + ix : b.zero_wire());
                         }
-                b.unit(field, K + (size_t)o * taps, T + o, 0, outs);
+                const int8_t *w = K + (size_t)o * taps;
+                const bool dense_row = std::all_of(w, w + taps, [](int8_t v) { return v != 0; });
+                if ((flags & TFHE_LOWER_PLUS_ONE) && taps > 1 && dense_row) {
+                    Number &X = field_sum[(size_t)y * Wo + x];
+                    if (X.bits.empty()) X = b.popcount(field);
+                    const Sig s = b.at_least_plus_one(field, w, T[o], X);
+                    outs.push_back(tfhe_out_ref{s.wire, s.flag});
+                } else {
+                    b.unit(field, w, T + o, 0, outs);
+                }
             }
     return TFHE_OK;
 }
@@ -284,11 +349,18 @@ int bnn_dense_lower_opts(int d, const int8_t *W, const int32_t *T, int p, int ou
 int bnn_conv_lower(int C, int H, int Wd, const int8_t *K, int O, int kh, int kw, int stride, int pad,
                    const int32_t *T, tfhe_gate_rec **gates, size_t *ngates, tfhe_out_ref **outs, size_t *nouts,
                    size_t *nwires) {
+    return bnn_conv_lower_opts(C, H, Wd, K, O, kh, kw, stride, pad, T, TFHE_LOWER_DEFAULT, gates, ngates, outs,
+                               nouts, nwires);
+}
+
+int bnn_conv_lower_opts(int C, int H, int Wd, const int8_t *K, int O, int kh, int kw, int stride, int pad,
+                        const int32_t *T, uint32_t flags, tfhe_gate_rec **gates, size_t *ngates,
+                        tfhe_out_ref **outs, size_t *nouts, size_t *nwires) {
     if (!gates || !ngates || !outs || !nouts || !nwires) return set_error(TFHE_E_NULL, "NULL output pointer");
     if (C < 1 || H < 1 || Wd < 1) return set_error(TFHE_E_SIZE, "bad convolution shape");
     Builder b(C * H * Wd);
     std::vector<tfhe_out_ref> o;
-    if (int rc = lower_conv(C, H, Wd, K, O, kh, kw, stride, pad, T, b, o)) return rc;
+    if (int rc = lower_conv(C, H, Wd, K, O, kh, kw, stride, pad, T, flags, b, o)) return rc;
     if (int rc = hand_over(b.gates(), gates, ngates)) return rc;
     if (int rc = hand_over(o, outs, nouts)) { free(*gates); return rc; }
     *nwires = (size_t)b.wires();
@@ -313,12 +385,18 @@ int bnn_dense_encrypted_opts(tfhe_cloud_key *ck, const uint32_t *x, int d, const
 
 int bnn_conv_encrypted(tfhe_cloud_key *ck, const uint32_t *x, int C, int H, int Wd, const int8_t *K, int O,
                        int kh, int kw, int stride, int pad, const int32_t *T, uint32_t *out, void *stream) {
+    return bnn_conv_encrypted_opts(ck, x, C, H, Wd, K, O, kh, kw, stride, pad, T, out, TFHE_LOWER_DEFAULT, stream);
+}
+
+int bnn_conv_encrypted_opts(tfhe_cloud_key *ck, const uint32_t *x, int C, int H, int Wd, const int8_t *K, int O,
+                            int kh, int kw, int stride, int pad, const int32_t *T, uint32_t *out, uint32_t flags,
+                            void *stream) {
     if (int rc = tfhe::ensure_uploaded(ck)) return rc;
     if (!x || !out) return set_error(TFHE_E_NULL, "NULL ciphertext buffer");
     if (C < 1 || H < 1 || Wd < 1) return set_error(TFHE_E_SIZE, "bad convolution shape");
     Builder b(C * H * Wd);
     std::vector<tfhe_out_ref> o;
-    if (int rc = lower_conv(C, H, Wd, K, O, kh, kw, stride, pad, T, b, o)) return rc;
+    if (int rc = lower_conv(C, H, Wd, K, O, kh, kw, stride, pad, T, flags, b, o)) return rc;
     return evaluate(ck, b, o, x, C * H * Wd, out, (hipStream_t)stream);
 }
 

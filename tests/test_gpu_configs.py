@@ -196,3 +196,46 @@ def test_small_convolution_entry_point(gpu, real_keys):
         else:
             for k, (oc, y, xx) in enumerate(pixels):
                 assert np.array_equal(got[(oc * Ho + y) * Wo + xx], ref[k])
+
+
+def test_plus_one_trick_layers(gpu, real_keys):
+    """The '+1' lowering: small dense and convolution layers byte for byte against the oracle's own
+    '+1' circuits; the full 784 -> 512 layer decrypted against the integer layer."""
+    import torch
+    T, sk, ck = gpu
+    rng = np.random.default_rng(101)
+    d, p = 13, 4
+    W = (2 * rng.integers(0, 2, (p, d)) - 1).astype(np.int8)
+    W[3, 2] = 0                                            # falls back to the plain unit
+    Tt = np.array([5, 7, 9, 6], np.int32)
+    x = rng.integers(0, 2, d).astype(np.uint8)
+    ctx = T.tfhe_encrypt(sk, 102, x)
+    out = torch.empty((p, 501), dtype=torch.int32, device="cuda")
+    T.bnn_dense_encrypted_opts(ck, T.to_device(ctx), d, W, Tt, p, out, 0, T.LOWER_PLUS_ONE)
+    torch.cuda.synchronize()
+    cir, o = cc.dense_layer(d, W, Tt, plus_one=True)
+    ref, _ = cc.eval_encrypted(real_keys, cir, ctx, o, threads=16)
+    assert np.array_equal(T.to_host(out), ref)
+    assert np.array_equal(T.tfhe_decrypt(sk, T.to_host(out)), cc.dense_plain(x, W, Tt))
+
+    xi = rng.integers(0, 2, (2, 4, 3)).astype(np.uint8)
+    K = (2 * rng.integers(0, 2, (3, 2, 3, 3)) - 1).astype(np.int8)
+    Tc = np.array([8, 9, 10], np.int32)
+    cti = T.tfhe_encrypt(sk, 103, xi.reshape(-1))
+    outc = torch.empty((3 * 4 * 3, 501), dtype=torch.int32, device="cuda")
+    T.bnn_conv_encrypted_opts(ck, T.to_device(cti), 2, 4, 3, K, Tc, 1, 1, outc, T.LOWER_PLUS_ONE)
+    torch.cuda.synchronize()
+    pixels = [(0, 0, 0), (2, 3, 2), (1, 1, 1)]
+    cir, o = cc.conv_layer(2, 4, 3, K, Tc, 1, 1, pixels=pixels, plus_one=True)
+    ref, _ = cc.eval_encrypted(real_keys, cir, cti, o, threads=16)
+    got = T.to_host(outc)
+    for k, (oc, y, xx) in enumerate(pixels):
+        assert np.array_equal(got[(oc * 4 + y) * 3 + xx], ref[k])
+    assert np.array_equal(T.tfhe_decrypt(sk, got).reshape(3, 4, 3), cc.conv_plain(xi, K, Tc, 1, 1))
+
+    c = workloads.cfg3()
+    xd = T.to_device(T.tfhe_encrypt(sk, c["enc_seed"], c["x"]))
+    big = torch.empty((512, 501), dtype=torch.int32, device="cuda")
+    T.bnn_dense_encrypted_opts(ck, xd, 784, c["W"], c["T"], 512, big, 0, T.LOWER_PLUS_ONE)
+    torch.cuda.synchronize()
+    assert np.array_equal(T.tfhe_decrypt(sk, T.to_host(big)), cc.dense_plain(c["x"], c["W"], c["T"]))

@@ -134,6 +134,26 @@ def test_mux_comparator_lowering_is_the_oracle_circuit(d, p):
         T.bnn_dense_lower_opts(d, W, Tt, p, 0, 8)
 
 
+@pytest.mark.parametrize("d,p", [(2, 2), (7, 5), (33, 4), (144, 3), (784, 2)])
+def test_plus_one_lowering_is_the_oracle_circuit(d, p):
+    rng = np.random.default_rng(7 * d)
+    W = (2 * rng.integers(0, 2, (p, d)) - 1).astype(np.int8)
+    if d > 2:
+        W[p - 1, 1] = 0                                   # this row falls back to the plain unit
+    Tt = rng.integers(-1, d + 2, p).astype(np.int32)
+    gates, outs, nw = T.bnn_dense_lower_opts(d, W, Tt, p, 0, T.LOWER_PLUS_ONE)
+    cir, o = cc.dense_layer(d, W, Tt, plus_one=True)
+    assert nw == cir.n_wires and len(gates) == len(cir.gates)
+    mine = canonical(gates, [(int(r["wire"]), int(r["value"])) for r in outs], nw, d)
+    assert mine == canonical(cir.gate_array(), oracle_outs(o), cir.n_wires, d)
+    c4 = workloads.cfg4(C=2, H=4, Wd=3, O=4)
+    gates, outs, nw = T.bnn_conv_lower_opts(2, 4, 3, c4["K"], c4["T"] // 8, 1, 1, T.LOWER_PLUS_ONE)
+    cir, o = cc.conv_layer(2, 4, 3, c4["K"], c4["T"] // 8, 1, 1, plus_one=True)
+    assert nw == cir.n_wires
+    assert canonical(gates, [(int(r["wire"]), int(r["value"])) for r in outs], nw, 24) == \
+        canonical(cir.gate_array(), oracle_outs(o), cir.n_wires, 24)
+
+
 def test_conv_lowering_is_the_oracle_circuit():
     c4 = workloads.cfg4(C=2, H=4, Wd=5, O=3)
     gates, outs, nw = T.bnn_conv_lower(2, 4, 5, c4["K"], c4["T"] // 8, 1, 1)
