@@ -40,6 +40,8 @@ def main():
                          "Algorithm 1 as printed, one MUX gate per popcount bit")
     ap.add_argument("--plus-one", action="store_true",
                     help="lower the layer with the '+1' trick (half-size trees on one shared input popcount)")
+    ap.add_argument("--share", action="store_true",
+                    help="emit identical gates of different units once (structural sharing)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--cpu-gates", type=int, default=512, help="gates in the oracle sample")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
@@ -79,6 +81,9 @@ def main():
         if args.plus_one:
             flags |= T.LOWER_PLUS_ONE
             name += ", '+1' trick"
+        if args.share:
+            flags |= T.LOWER_SHARE_GATES
+            name += ", shared gates"
         gates_host, _, _ = T.bnn_dense_lower_opts(d, c["W"], c["T"], p, 0, flags)
         # a multiplexer is two records (two blind rotations) but one gate
         gates_per_step = int((gates_host["op"] != T.MUX_ELSE).sum())

@@ -182,7 +182,11 @@ enum { TFHE_LOWER_DEFAULT = 0,
         * The subtraction is an addition of the negated (complemented) bits, the factor 2 a shift,
         * so each unit costs a half-size tree, one ripple-carry adder and the threshold chain.
         * Units with a zero weight are lowered the default way. */
-       TFHE_LOWER_PLUS_ONE = 2 };
+       TFHE_LOWER_PLUS_ONE = 2,
+       /* emit a two-input gate only once per (opcode, unordered pair of possibly negated input
+        * wires): units that read the same inputs share the lowest levels of their trees, where
+        * only the 4 sign patterns of each input pair occur (not in the paper) */
+       TFHE_LOWER_SHARE_GATES = 4 };
 int bnn_dense_lower_opts(int d, const int8_t *W, const int32_t *T, int p, int out_bits, uint32_t flags,
                          tfhe_gate_rec **gates, size_t *ngates, tfhe_out_ref **outs, size_t *nouts,
                          size_t *nwires);

@@ -26,14 +26,23 @@ class Circuit:
     wire n_inputs is a noiseless encryption of 0, wire n_inputs+1 of 1, every gate
     appends one wire.  A literal is (wire, neg)."""
 
-    def __init__(self, n_inputs):
+    def __init__(self, n_inputs, share=False):
         self.n_inputs = n_inputs
         self.c0 = n_inputs
         self.c1 = n_inputs + 1
         self.n_wires = n_inputs + 2
         self.gates = []
+        # share=True: a two-input gate with the same opcode and the same unordered pair of
+        # (wire, negation) inputs as an earlier one is not emitted again; its wire is reused
+        self.share = share
+        self.known = {}
 
     def gate(self, op, a, b):
+        if self.share:
+            key = (OP[op],) + tuple(sorted((a, b)))
+            if key in self.known:
+                return self.known[key]
+            self.known[key] = (self.n_wires, 0)
         out = self.n_wires
         self.n_wires += 1
         self.gates.append((OP[op], a[1], b[1], 0, a[0], b[0], out))
@@ -198,10 +207,11 @@ def neuron(cir, x_literals, w_row, T, out_bits=0, comparator="folded"):
     return bits
 
 
-def dense_layer(d, W, T, out_bits=0, comparator="folded", plus_one=False):
+def dense_layer(d, W, T, out_bits=0, comparator="folded", plus_one=False, share=False):
     """Circuit of a fully connected layer.  Returns (circuit, outputs).  With plus_one the rows
-    without zero weights use the '+1' trick on one shared popcount of the inputs."""
-    cir = Circuit(d)
+    without zero weights use the '+1' trick on one shared popcount of the inputs; with share
+    identical gates of different units are emitted once."""
+    cir = Circuit(d, share)
     x = [(i, 0) for i in range(d)]
     outs = []
     X = None
@@ -230,13 +240,13 @@ def conv_pixel_literals(cir, C_, H, Wd, kh, kw, stride, pad, y, x):
     return lits
 
 
-def conv_layer(C_, H, Wd, K, T, stride, pad, pixels=None, plus_one=False):
+def conv_layer(C_, H, Wd, K, T, stride, pad, pixels=None, plus_one=False, share=False):
     """Circuit of a convolution layer (or of the listed output pixels (o, y, x) only).  With
     plus_one the popcount of a receptive field is shared by the output channels of its pixel."""
     O, _, kh, kw = K.shape
     Ho = (H + 2 * pad - kh) // stride + 1
     Wo = (Wd + 2 * pad - kw) // stride + 1
-    cir = Circuit(C_ * H * Wd)
+    cir = Circuit(C_ * H * Wd, share)
     if pixels is None:
         pixels = [(o, y, x) for o in range(O) for y in range(Ho) for x in range(Wo)]
     outs = []

@@ -43,12 +43,21 @@ struct Number {
 
 class Builder {
 public:
-    explicit Builder(int32_t n_inputs) : next_(n_inputs + 2), zero_(n_inputs), one_(n_inputs + 1) {}
+    explicit Builder(int32_t n_inputs, bool share = false)
+        : next_(n_inputs + 2), zero_(n_inputs), one_(n_inputs + 1), share_(share) {}
     int32_t zero_wire() const { return zero_; }
     int32_t wires() const { return next_; }
     std::vector<tfhe_gate_rec> &gates() { return gates_; }
 
     Sig emit(int op, Sig a, Sig b) {
+        if (share_) {
+            // same opcode on the same unordered pair of literals: reuse the earlier gate's wire
+            const uint64_t la = ((uint64_t)(uint32_t)a.wire << 1) | (uint64_t)a.flag;   // < 2^32
+            const uint64_t lb = ((uint64_t)(uint32_t)b.wire << 1) | (uint64_t)b.flag;
+            int32_t &slot = known_.slot(op, (std::min(la, lb) << 32) | std::max(la, lb));
+            if (slot >= 0) return Sig::of(slot);
+            slot = next_;
+        }
         tfhe_gate_rec r{};
         r.op = (uint8_t)op; r.neg0 = (uint8_t)a.flag; r.neg1 = (uint8_t)b.flag;
         r.in0 = a.wire; r.in1 = b.wire; r.out = next_++;
@@ -215,6 +224,38 @@ public:
 private:
     std::vector<tfhe_gate_rec> gates_;
     int32_t next_, zero_, one_;
+    bool share_;
+
+    // open-addressing table (opcode, literal pair) -> wire; grows by doubling
+    struct GateTable {
+        std::vector<uint64_t> keys;
+        std::vector<int32_t> wires;      // -1 = empty slot
+        std::vector<uint8_t> ops;
+        size_t used = 0;
+        static size_t mix(uint64_t k, int op) {
+            k ^= (uint64_t)op * 0x9E3779B97F4A7C15ull;
+            k ^= k >> 32; k *= 0xD6E8FEB86659FD93ull; k ^= k >> 32;
+            return (size_t)k;
+        }
+        void grow() {
+            GateTable bigger;
+            const size_t cap = keys.empty() ? (size_t)1 << 16 : keys.size() * 2;
+            bigger.keys.assign(cap, 0); bigger.wires.assign(cap, -1); bigger.ops.assign(cap, 0);
+            for (size_t i = 0; i < keys.size(); ++i)
+                if (wires[i] >= 0) bigger.slot(ops[i], keys[i]) = wires[i];
+            bigger.used = used;
+            *this = std::move(bigger);
+        }
+        // the slot of (op, key): its wire if present, else an empty slot (value -1) to fill
+        int32_t &slot(int op, uint64_t key) {
+            if ((used + 1) * 10 >= keys.size() * 7) grow();
+            const size_t mask = keys.size() - 1;
+            for (size_t at = mix(key, op) & mask;; at = (at + 1) & mask) {
+                if (wires[at] < 0) { keys[at] = key; ops[at] = (uint8_t)op; ++used; return wires[at]; }
+                if (keys[at] == key && ops[at] == op) return wires[at];
+            }
+        }
+    } known_;
 };
 
 template <class T>
@@ -234,7 +275,7 @@ int check_weights(const int8_t *W, size_t count) {
 
 int lower_dense(int d, const int8_t *W, const int32_t *T, int p, int out_bits, uint32_t flags, Builder &b,
                 std::vector<tfhe_out_ref> &outs) {
-    if (flags & ~(uint32_t)(TFHE_LOWER_MUX_COMPARATOR | TFHE_LOWER_PLUS_ONE))
+    if (flags & ~(uint32_t)(TFHE_LOWER_MUX_COMPARATOR | TFHE_LOWER_PLUS_ONE | TFHE_LOWER_SHARE_GATES))
         return set_error(TFHE_E_PARAM, "unknown lowering flags %u", flags);
     if (d < 1 || p < 1) return set_error(TFHE_E_SIZE, "layer sizes must be positive");
     if (!W) return set_error(TFHE_E_NULL, "W is NULL");
@@ -269,7 +310,8 @@ int lower_dense(int d, const int8_t *W, const int32_t *T, int p, int out_bits, u
 
 int lower_conv(int C, int H, int Wd, const int8_t *K, int O, int kh, int kw, int stride, int pad,
                const int32_t *T, uint32_t flags, Builder &b, std::vector<tfhe_out_ref> &outs) {
-    if (flags & ~(uint32_t)TFHE_LOWER_PLUS_ONE) return set_error(TFHE_E_PARAM, "unknown lowering flags %u", flags);
+    if (flags & ~(uint32_t)(TFHE_LOWER_PLUS_ONE | TFHE_LOWER_SHARE_GATES))
+        return set_error(TFHE_E_PARAM, "unknown lowering flags %u", flags);
     if (C < 1 || H < 1 || Wd < 1 || O < 1 || kh < 1 || kw < 1 || stride < 1 || pad < 0)
         return set_error(TFHE_E_SIZE, "bad convolution shape");
     if (!K || !T) return set_error(TFHE_E_NULL, "K or T is NULL");
@@ -337,7 +379,7 @@ int bnn_dense_lower_opts(int d, const int8_t *W, const int32_t *T, int p, int ou
                          size_t *nwires) {
     if (!gates || !ngates || !outs || !nouts || !nwires) return set_error(TFHE_E_NULL, "NULL output pointer");
     if (d < 1) return set_error(TFHE_E_SIZE, "layer sizes must be positive");
-    Builder b(d);
+    Builder b(d, (flags & TFHE_LOWER_SHARE_GATES) != 0);
     std::vector<tfhe_out_ref> o;
     if (int rc = lower_dense(d, W, T, p, out_bits, flags, b, o)) return rc;
     if (int rc = hand_over(b.gates(), gates, ngates)) return rc;
@@ -358,7 +400,7 @@ int bnn_conv_lower_opts(int C, int H, int Wd, const int8_t *K, int O, int kh, in
                         tfhe_out_ref **outs, size_t *nouts, size_t *nwires) {
     if (!gates || !ngates || !outs || !nouts || !nwires) return set_error(TFHE_E_NULL, "NULL output pointer");
     if (C < 1 || H < 1 || Wd < 1) return set_error(TFHE_E_SIZE, "bad convolution shape");
-    Builder b(C * H * Wd);
+    Builder b(C * H * Wd, (flags & TFHE_LOWER_SHARE_GATES) != 0);
     std::vector<tfhe_out_ref> o;
     if (int rc = lower_conv(C, H, Wd, K, O, kh, kw, stride, pad, T, flags, b, o)) return rc;
     if (int rc = hand_over(b.gates(), gates, ngates)) return rc;
@@ -377,7 +419,7 @@ int bnn_dense_encrypted_opts(tfhe_cloud_key *ck, const uint32_t *x, int d, const
     if (int rc = tfhe::ensure_uploaded(ck)) return rc;
     if (!x || !out) return set_error(TFHE_E_NULL, "NULL ciphertext buffer");
     if (d < 1) return set_error(TFHE_E_SIZE, "layer sizes must be positive");
-    Builder b(d);
+    Builder b(d, (flags & TFHE_LOWER_SHARE_GATES) != 0);
     std::vector<tfhe_out_ref> o;
     if (int rc = lower_dense(d, W, T, p, out_bits, flags, b, o)) return rc;
     return evaluate(ck, b, o, x, d, out, (hipStream_t)stream);
@@ -394,7 +436,7 @@ int bnn_conv_encrypted_opts(tfhe_cloud_key *ck, const uint32_t *x, int C, int H,
     if (int rc = tfhe::ensure_uploaded(ck)) return rc;
     if (!x || !out) return set_error(TFHE_E_NULL, "NULL ciphertext buffer");
     if (C < 1 || H < 1 || Wd < 1) return set_error(TFHE_E_SIZE, "bad convolution shape");
-    Builder b(C * H * Wd);
+    Builder b(C * H * Wd, (flags & TFHE_LOWER_SHARE_GATES) != 0);
     std::vector<tfhe_out_ref> o;
     if (int rc = lower_conv(C, H, Wd, K, O, kh, kw, stride, pad, T, flags, b, o)) return rc;
     return evaluate(ck, b, o, x, C * H * Wd, out, (hipStream_t)stream);

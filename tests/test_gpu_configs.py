@@ -239,3 +239,30 @@ def test_plus_one_trick_layers(gpu, real_keys):
     T.bnn_dense_encrypted_opts(ck, xd, 784, c["W"], c["T"], 512, big, 0, T.LOWER_PLUS_ONE)
     torch.cuda.synchronize()
     assert np.array_equal(T.tfhe_decrypt(sk, T.to_host(big)), cc.dense_plain(c["x"], c["W"], c["T"]))
+
+
+def test_shared_gate_lowering(gpu, real_keys):
+    """Gate sharing across units: a small layer byte for byte against the oracle's shared
+    circuit, and the full 784 -> 512 layer ('+1' trick and sharing together: 1.04 M gates instead
+    of 2.79 M) decrypted against the integer layer."""
+    import torch
+    T, sk, ck = gpu
+    rng = np.random.default_rng(111)
+    d, p = 16, 6
+    W = (2 * rng.integers(0, 2, (p, d)) - 1).astype(np.int8)
+    Tt = rng.integers(5, 12, p).astype(np.int32)
+    x = rng.integers(0, 2, d).astype(np.uint8)
+    ctx = T.tfhe_encrypt(sk, 112, x)
+    out = torch.empty((p, 501), dtype=torch.int32, device="cuda")
+    T.bnn_dense_encrypted_opts(ck, T.to_device(ctx), d, W, Tt, p, out, 0, T.LOWER_SHARE_GATES)
+    torch.cuda.synchronize()
+    cir, o = cc.dense_layer(d, W, Tt, share=True)
+    assert len(cir.gates) < len(cc.dense_layer(d, W, Tt)[0].gates)
+    ref, _ = cc.eval_encrypted(real_keys, cir, ctx, o, threads=16)
+    assert np.array_equal(T.to_host(out), ref)
+    c = workloads.cfg3()
+    xd = T.to_device(T.tfhe_encrypt(sk, c["enc_seed"], c["x"]))
+    big = torch.empty((512, 501), dtype=torch.int32, device="cuda")
+    T.bnn_dense_encrypted_opts(ck, xd, 784, c["W"], c["T"], 512, big, 0, T.LOWER_SHARE_GATES | T.LOWER_PLUS_ONE)
+    torch.cuda.synchronize()
+    assert np.array_equal(T.tfhe_decrypt(sk, T.to_host(big)), cc.dense_plain(c["x"], c["W"], c["T"]))

@@ -154,6 +154,33 @@ def test_plus_one_lowering_is_the_oracle_circuit(d, p):
         canonical(cir.gate_array(), oracle_outs(o), cir.n_wires, 24)
 
 
+@pytest.mark.parametrize("plus_one", [False, True])
+def test_shared_gate_lowering_is_the_oracle_circuit(plus_one):
+    rng = np.random.default_rng(17)
+    d, p = 48, 12
+    W = (2 * rng.integers(0, 2, (p, d)) - 1).astype(np.int8)
+    Tt = rng.integers(10, 40, p).astype(np.int32)
+    flags = T.LOWER_SHARE_GATES | (T.LOWER_PLUS_ONE if plus_one else 0)
+    gates, outs, nw = T.bnn_dense_lower_opts(d, W, Tt, p, 0, flags)
+    cir, o = cc.dense_layer(d, W, Tt, plus_one=plus_one, share=True)
+    unshared = len(cc.dense_layer(d, W, Tt, plus_one=plus_one)[0].gates)
+    assert nw == cir.n_wires and len(gates) == len(cir.gates) < unshared
+    assert canonical(gates, [(int(r["wire"]), int(r["value"])) for r in outs], nw, d) == \
+        canonical(cir.gate_array(), oracle_outs(o), cir.n_wires, d)
+    # no (opcode, unordered literal pair) occurs twice
+    keys = {(int(g["op"]),) + tuple(sorted(((int(g["in0"]), int(g["neg0"])), (int(g["in1"]), int(g["neg1"]))))) for g in gates}
+    assert len(keys) == len(gates)
+    for _ in range(4):
+        x = rng.integers(0, 2, d).astype(np.uint8)
+        assert np.array_equal(cc.eval_plain(cir, x, o), cc.dense_plain(x, W, Tt))
+    c4 = workloads.cfg4(C=2, H=4, Wd=3, O=6)
+    gates, outs, nw = T.bnn_conv_lower_opts(2, 4, 3, c4["K"], c4["T"] // 8, 1, 1, flags)
+    cir, o = cc.conv_layer(2, 4, 3, c4["K"], c4["T"] // 8, 1, 1, plus_one=plus_one, share=True)
+    assert nw == cir.n_wires and len(gates) == len(cir.gates)
+    assert canonical(gates, [(int(r["wire"]), int(r["value"])) for r in outs], nw, 24) == \
+        canonical(cir.gate_array(), oracle_outs(o), cir.n_wires, 24)
+
+
 def test_conv_lowering_is_the_oracle_circuit():
     c4 = workloads.cfg4(C=2, H=4, Wd=5, O=3)
     gates, outs, nw = T.bnn_conv_lower(2, 4, 5, c4["K"], c4["T"] // 8, 1, 1)
