@@ -188,6 +188,74 @@ def neuron_plus_one(cir, x_literals, w_row, T, X):
     return [threshold_chain(cir, U, c + offset)]
 
 
+def sorting_network_unit(cir, leaves, T):
+    """[S >= T] by sorting the XNOR bits (Sec. 4.1.1 'Sorting network'): after a descending sort
+    the bit at position T-1 is 1 exactly when at least T inputs are 1.  The network is Batcher's
+    bitonic sorter on the next power of two (padded with noiseless zeros at the end), every
+    compare-exchange SWAP(a, b) = (OR(a, b), AND(a, b)) moving the larger bit to the lower index:
+    for block sizes k = 2, 4, ..., n first the pairs (i, i XOR (k-1)), then (i, i XOR j) for
+    j = k/4, k/8, ..., 1.  A swap with a known zero needs no gate (OR(a,0) = a, AND(a,0) = 0), and
+    only the gates that the selected position depends on are emitted."""
+    m = len(leaves)
+    if T <= 0:
+        return CONST1
+    if T > m:
+        return CONST0
+    n = 1
+    while n < m:
+        n *= 2
+    # local network: entries are ('lit', literal), ('zero',) or ('gate', index into local list)
+    a = [("lit", l) for l in leaves] + [("zero",)] * (n - m)
+    local = []                                             # (op, entry, entry)
+
+    def swap(i, l):
+        x, y = a[i], a[l]
+        if y[0] == "zero":
+            return
+        if x[0] == "zero":
+            a[i], a[l] = y, x
+            return
+        local.append(("OR", x, y))
+        local.append(("AND", x, y))
+        a[i], a[l] = ("gate", len(local) - 2), ("gate", len(local) - 1)
+
+    k = 2
+    while k <= n:
+        for i in range(n):
+            l = i ^ (k - 1)
+            if l > i:
+                swap(i, l)
+        j = k // 4
+        while j >= 1:
+            for i in range(n):
+                l = i ^ j
+                if l > i:
+                    swap(i, l)
+            j //= 2
+        k *= 2
+    out = a[T - 1]
+    if out[0] == "lit":
+        return out[1]
+    assert out[0] == "gate"
+    needed = [False] * len(local)
+    stack = [out[1]]
+    while stack:
+        g = stack.pop()
+        if needed[g]:
+            continue
+        needed[g] = True
+        for e in local[g][1:]:
+            if e[0] == "gate":
+                stack.append(e[1])
+    wire = {}
+    for g, (op, x, y) in enumerate(local):
+        if needed[g]:
+            lx = x[1] if x[0] == "lit" else wire[x[1]]
+            ly = y[1] if y[0] == "lit" else wire[y[1]]
+            wire[g] = cir.gate(op, lx, ly)
+    return wire[out[1]]
+
+
 def neuron(cir, x_literals, w_row, T, out_bits=0, comparator="folded"):
     """One output unit.  x_literals[i] is the literal of input i; w in {-1,0,+1}.
     Returns one literal/constant (T given) or out_bits popcount literals (T None)."""
@@ -197,6 +265,8 @@ def neuron(cir, x_literals, w_row, T, out_bits=0, comparator="folded"):
             leaves.append(lit)
         elif w < 0:
             leaves.append((lit[0], lit[1] ^ 1))
+    if T is not None and comparator == "sort":
+        return [sorting_network_unit(cir, leaves, int(T))]
     S = popcount_tree(cir, leaves)
     if T is not None:
         if comparator == "mux":

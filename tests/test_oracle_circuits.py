@@ -313,3 +313,38 @@ def test_plus_one_encrypted_toy(orc, toy_keys):
     cir, outs = cc.dense_layer(d, W, T, plus_one=True)
     res, _ = cc.eval_encrypted(toy_keys, cir, ct, outs, threads=4)
     assert np.array_equal(toy_keys.decrypt(res), cc.dense_plain(x, W, T))
+
+
+# --------------------------------------------------------------------------- sorting network
+def test_swap_sorts_two_bits():
+    """SWAP(a, b) = (OR(a, b), AND(a, b)) is (max, min) (Sec. 4.1.1)."""
+    for a, b in itertools.product((0, 1), repeat=2):
+        assert (a | b, a & b) == (max(a, b), min(a, b))
+
+
+@pytest.mark.parametrize("m", [1, 2, 3, 4, 5, 6, 7, 8, 9, 11])
+def test_sorting_network_unit_exhaustive(m):
+    rng = np.random.default_rng(m)
+    w = (2 * rng.integers(0, 2, m) - 1).astype(np.int8)
+    for T in range(-1, m + 3):
+        cir = cc.Circuit(m)
+        outs = cc.neuron(cir, [(i, 0) for i in range(m)], w, T, comparator="sort")
+        for bits in itertools.product((0, 1), repeat=m):
+            x = np.array(bits, np.uint8)
+            assert cc.eval_plain(cir, x, outs)[0] == cc.dense_plain(x, w.reshape(1, m), np.array([T]))[0]
+
+
+@pytest.mark.parametrize("m", [16, 33, 100, 144, 256])
+def test_sorting_network_unit_random_and_size(m):
+    rng = np.random.default_rng(m)
+    w = rng.choice(np.array([-1, 0, 1], np.int8), m, p=[0.45, 0.1, 0.45])
+    live = int((w != 0).sum())
+    n = 1 << (live - 1).bit_length()
+    full = 2 * (n // 4) * n.bit_length() * (n.bit_length() - 1)      # 2 gates x (n/4) log n (log n + 1) swaps
+    for T in (1, live // 3, live // 2, live):
+        cir = cc.Circuit(m)
+        outs = cc.neuron(cir, [(i, 0) for i in range(m)], w, T, comparator="sort")
+        assert len(cir.gates) <= full
+        for _ in range(5):
+            x = rng.integers(0, 2, m).astype(np.uint8)
+            assert cc.eval_plain(cir, x, outs)[0] == cc.dense_plain(x, w.reshape(1, m), np.array([T]))[0]
