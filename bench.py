@@ -35,9 +35,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="cfg3", choices=["cfg3", "cfg2", "flat"])
     ap.add_argument("--flat-count", type=int, default=65536)
-    ap.add_argument("--comparator", default="folded", choices=["folded", "mux"],
+    ap.add_argument("--comparator", default="folded", choices=["folded", "mux", "sort"],
                     help="threshold circuit: AND/OR chain folded by the plaintext bits (default) or "
-                         "Algorithm 1 as printed, one MUX gate per popcount bit")
+                         "Algorithm 1 as printed, one MUX gate per popcount bit; 'sort' replaces tree and "
+                         "comparator by the bitonic sorting network")
     ap.add_argument("--plus-one", action="store_true",
                     help="lower the layer with the '+1' trick (half-size trees on one shared input popcount)")
     ap.add_argument("--share", action="store_true",
@@ -77,7 +78,8 @@ def main():
         p, d = c["W"].shape
         x = T.to_device(T.tfhe_encrypt(sk, c["enc_seed"], c["x"]))
         out = torch.empty((p, words), dtype=torch.int32, device="cuda")
-        flags = T.LOWER_MUX_COMPARATOR if args.comparator == "mux" else T.LOWER_DEFAULT
+        flags = {"folded": T.LOWER_DEFAULT, "mux": T.LOWER_MUX_COMPARATOR,
+                 "sort": T.LOWER_SORTING_NETWORK}[args.comparator]
         if args.plus_one:
             flags |= T.LOWER_PLUS_ONE
             name += ", '+1' trick"
@@ -89,6 +91,8 @@ def main():
         gates_per_step = int((gates_host["op"] != T.MUX_ELSE).sum())
         if args.comparator == "mux":
             name += ", Algorithm-1 MUX comparator"
+        if args.comparator == "sort":
+            name += ", sorting network"
 
         def step():
             T.bnn_dense_encrypted_opts(ck, x, d, c["W"], c["T"], p, out, 0, flags)

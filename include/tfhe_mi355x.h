@@ -186,7 +186,13 @@ enum { TFHE_LOWER_DEFAULT = 0,
        /* emit a two-input gate only once per (opcode, unordered pair of possibly negated input
         * wires): units that read the same inputs share the lowest levels of their trees, where
         * only the 4 sign patterns of each input pair occur (not in the paper) */
-       TFHE_LOWER_SHARE_GATES = 4 };
+       TFHE_LOWER_SHARE_GATES = 4,
+       /* the alternative inner-product circuit of Sec. 4.1.1: sort the XNOR bits in descending
+        * order with Batcher's bitonic network of SWAP(a,b) = (OR(a,b), AND(a,b)) and return the bit
+        * at position T-1.  The input is padded with noiseless zeros to a power of two; a swap with
+        * a known zero needs no gate; only gates the selected position depends on are emitted.
+        * Not combinable with TFHE_LOWER_MUX_COMPARATOR / TFHE_LOWER_PLUS_ONE; ignored when T is NULL. */
+       TFHE_LOWER_SORTING_NETWORK = 8 };
 int bnn_dense_lower_opts(int d, const int8_t *W, const int32_t *T, int p, int out_bits, uint32_t flags,
                          tfhe_gate_rec **gates, size_t *ngates, tfhe_out_ref **outs, size_t *nouts,
                          size_t *nwires);

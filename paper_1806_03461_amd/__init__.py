@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(HERE, "libtfhe_mi355x.so")
 
 NAND, AND, OR, NOR, XOR, XNOR, MUX, MUX_ELSE = range(8)
 OPS = {"NAND": NAND, "AND": AND, "OR": OR, "NOR": NOR, "XOR": XOR, "XNOR": XNOR}
-LOWER_DEFAULT, LOWER_MUX_COMPARATOR, LOWER_PLUS_ONE, LOWER_SHARE_GATES = 0, 1, 2, 4
+LOWER_DEFAULT, LOWER_MUX_COMPARATOR, LOWER_PLUS_ONE, LOWER_SHARE_GATES, LOWER_SORTING_NETWORK = 0, 1, 2, 4, 8
 KEY_LWE_SK, KEY_TRLWE_SK, KEY_BK_RAW, KEY_KSK_RAW = range(4)
 
 GATE_DTYPE = np.dtype([("op", "u1"), ("neg0", "u1"), ("neg1", "u1"), ("pad", "u1"),

@@ -198,6 +198,56 @@ public:
         return at_least(U, c + offset);
     }
 
+    // [at least T of the leaves are 1] as position T-1 of a descending bitonic sort
+    Sig at_least_by_sorting(const std::vector<Sig> &leaves, int64_t T) {
+        const size_t m = leaves.size();
+        if (T <= 0) return Sig::constant(1);
+        if (T > (int64_t)m) return Sig::constant(0);
+        size_t n = 1;
+        while (n < m) n *= 2;
+        // network entries: a literal, a known zero, or the output of a local (not yet emitted) gate
+        struct Entry { int kind; Sig lit; int32_t gate; };     // kind 0 literal, 1 zero, 2 local gate
+        struct Local { int op; Entry x, y; };
+        std::vector<Entry> a(n, Entry{1, Sig::constant(0), -1});
+        for (size_t i = 0; i < m; ++i) a[i] = Entry{0, leaves[i], -1};
+        std::vector<Local> local;
+        auto swap_pair = [&](size_t i, size_t l) {
+            const Entry x = a[i], y = a[l];
+            if (y.kind == 1) return;
+            if (x.kind == 1) { a[i] = y; a[l] = x; return; }
+            local.push_back(Local{TFHE_OR, x, y});
+            local.push_back(Local{TFHE_AND, x, y});
+            a[i] = Entry{2, Sig::constant(0), (int32_t)local.size() - 2};
+            a[l] = Entry{2, Sig::constant(0), (int32_t)local.size() - 1};
+        };
+        for (size_t k = 2; k <= n; k *= 2) {
+            for (size_t i = 0; i < n; ++i) { const size_t l = i ^ (k - 1); if (l > i) swap_pair(i, l); }
+            for (size_t j = k / 4; j >= 1; j /= 2)
+                for (size_t i = 0; i < n; ++i) { const size_t l = i ^ j; if (l > i) swap_pair(i, l); }
+        }
+        const Entry out = a[(size_t)T - 1];
+        if (out.kind == 0) return out.lit;
+        // keep the cone of the selected position only, emit it in network order
+        std::vector<char> needed(local.size(), 0);
+        std::vector<int32_t> stack{out.gate};
+        while (!stack.empty()) {
+            const int32_t g = stack.back();
+            stack.pop_back();
+            if (needed[g]) continue;
+            needed[g] = 1;
+            if (local[g].x.kind == 2) stack.push_back(local[g].x.gate);
+            if (local[g].y.kind == 2) stack.push_back(local[g].y.gate);
+        }
+        std::vector<Sig> wire(local.size(), Sig::constant(0));
+        for (size_t g = 0; g < local.size(); ++g) {
+            if (!needed[g]) continue;
+            const Sig lx = local[g].x.kind == 0 ? local[g].x.lit : wire[local[g].x.gate];
+            const Sig ly = local[g].y.kind == 0 ? local[g].y.lit : wire[local[g].y.gate];
+            wire[g] = emit(local[g].op, lx, ly);
+        }
+        return wire[out.gate];
+    }
+
     // one output unit over the listed inputs
     void unit(const std::vector<Sig> &inputs, const int8_t *w, const int32_t *T, int out_bits,
               std::vector<tfhe_out_ref> &outs, uint32_t flags = 0) {
@@ -208,6 +258,11 @@ public:
             Sig s = inputs[i];
             if (w[i] < 0) s.flag ^= 1;
             leaves.push_back(s);
+        }
+        if (T && (flags & TFHE_LOWER_SORTING_NETWORK)) {
+            const Sig o = at_least_by_sorting(leaves, *T);
+            outs.push_back(tfhe_out_ref{o.wire, o.flag});
+            return;
         }
         const Number S = popcount(leaves);
         if (T) {
@@ -275,8 +330,11 @@ int check_weights(const int8_t *W, size_t count) {
 
 int lower_dense(int d, const int8_t *W, const int32_t *T, int p, int out_bits, uint32_t flags, Builder &b,
                 std::vector<tfhe_out_ref> &outs) {
-    if (flags & ~(uint32_t)(TFHE_LOWER_MUX_COMPARATOR | TFHE_LOWER_PLUS_ONE | TFHE_LOWER_SHARE_GATES))
+    if (flags & ~(uint32_t)(TFHE_LOWER_MUX_COMPARATOR | TFHE_LOWER_PLUS_ONE | TFHE_LOWER_SHARE_GATES |
+                            TFHE_LOWER_SORTING_NETWORK))
         return set_error(TFHE_E_PARAM, "unknown lowering flags %u", flags);
+    if ((flags & TFHE_LOWER_SORTING_NETWORK) && (flags & (TFHE_LOWER_MUX_COMPARATOR | TFHE_LOWER_PLUS_ONE)))
+        return set_error(TFHE_E_PARAM, "the sorting network excludes the MUX comparator and the +1 trick");
     if (d < 1 || p < 1) return set_error(TFHE_E_SIZE, "layer sizes must be positive");
     if (!W) return set_error(TFHE_E_NULL, "W is NULL");
     if (!T) {
@@ -310,8 +368,10 @@ int lower_dense(int d, const int8_t *W, const int32_t *T, int p, int out_bits, u
 
 int lower_conv(int C, int H, int Wd, const int8_t *K, int O, int kh, int kw, int stride, int pad,
                const int32_t *T, uint32_t flags, Builder &b, std::vector<tfhe_out_ref> &outs) {
-    if (flags & ~(uint32_t)(TFHE_LOWER_PLUS_ONE | TFHE_LOWER_SHARE_GATES))
+    if (flags & ~(uint32_t)(TFHE_LOWER_PLUS_ONE | TFHE_LOWER_SHARE_GATES | TFHE_LOWER_SORTING_NETWORK))
         return set_error(TFHE_E_PARAM, "unknown lowering flags %u", flags);
+    if ((flags & TFHE_LOWER_SORTING_NETWORK) && (flags & TFHE_LOWER_PLUS_ONE))
+        return set_error(TFHE_E_PARAM, "the sorting network excludes the +1 trick");
     if (C < 1 || H < 1 || Wd < 1 || O < 1 || kh < 1 || kw < 1 || stride < 1 || pad < 0)
         return set_error(TFHE_E_SIZE, "bad convolution shape");
     if (!K || !T) return set_error(TFHE_E_NULL, "K or T is NULL");
@@ -341,7 +401,7 @@ int lower_conv(int C, int H, int Wd, const int8_t *K, int O, int kh, int kw, int
                     const Sig s = b.at_least_plus_one(field, w, T[o], X);
                     outs.push_back(tfhe_out_ref{s.wire, s.flag});
                 } else {
-                    b.unit(field, w, T + o, 0, outs);
+                    b.unit(field, w, T + o, 0, outs, flags);
                 }
             }
     return TFHE_OK;

@@ -266,3 +266,22 @@ def test_shared_gate_lowering(gpu, real_keys):
     T.bnn_dense_encrypted_opts(ck, xd, 784, c["W"], c["T"], 512, big, 0, T.LOWER_SHARE_GATES | T.LOWER_PLUS_ONE)
     torch.cuda.synchronize()
     assert np.array_equal(T.tfhe_decrypt(sk, T.to_host(big)), cc.dense_plain(c["x"], c["W"], c["T"]))
+
+
+def test_sorting_network_layer(gpu, real_keys):
+    """The sorting-network inner product on the GPU against the oracle's own network, byte for byte."""
+    import torch
+    T, sk, ck = gpu
+    rng = np.random.default_rng(121)
+    d, p = 12, 3
+    W = rng.choice(np.array([-1, 0, 1], np.int8), (p, d), p=[0.45, 0.1, 0.45])
+    Tt = np.array([3, 6, 5], np.int32)
+    x = rng.integers(0, 2, d).astype(np.uint8)
+    ctx = T.tfhe_encrypt(sk, 122, x)
+    out = torch.empty((p, 501), dtype=torch.int32, device="cuda")
+    T.bnn_dense_encrypted_opts(ck, T.to_device(ctx), d, W, Tt, p, out, 0, T.LOWER_SORTING_NETWORK)
+    torch.cuda.synchronize()
+    cir, o = cc.dense_layer(d, W, Tt, comparator="sort")
+    ref, _ = cc.eval_encrypted(real_keys, cir, ctx, o, threads=16)
+    assert np.array_equal(T.to_host(out), ref)
+    assert np.array_equal(T.tfhe_decrypt(sk, T.to_host(out)), cc.dense_plain(x, W, Tt))

@@ -131,7 +131,7 @@ def test_mux_comparator_lowering_is_the_oracle_circuit(d, p):
     assert mine == canonical(cir.gate_array(), oracle_outs(o), cir.n_wires, d)
     assert (gates["op"] == T.MUX).sum() == (gates["op"] == T.MUX_ELSE).sum() > 0
     with pytest.raises(T.TfheError):
-        T.bnn_dense_lower_opts(d, W, Tt, p, 0, 8)
+        T.bnn_dense_lower_opts(d, W, Tt, p, 0, 64)
 
 
 @pytest.mark.parametrize("d,p", [(2, 2), (7, 5), (33, 4), (144, 3), (784, 2)])
@@ -179,6 +179,21 @@ def test_shared_gate_lowering_is_the_oracle_circuit(plus_one):
     assert nw == cir.n_wires and len(gates) == len(cir.gates)
     assert canonical(gates, [(int(r["wire"]), int(r["value"])) for r in outs], nw, 24) == \
         canonical(cir.gate_array(), oracle_outs(o), cir.n_wires, 24)
+
+
+@pytest.mark.parametrize("d,p", [(1, 2), (5, 3), (16, 3), (37, 4), (144, 2)])
+def test_sorting_network_lowering_is_the_oracle_circuit(d, p):
+    rng = np.random.default_rng(3 * d)
+    W = rng.choice(np.array([-1, 0, 1], np.int8), (p, d), p=[0.45, 0.1, 0.45])
+    Tt = rng.integers(-1, d + 2, p).astype(np.int32)
+    gates, outs, nw = T.bnn_dense_lower_opts(d, W, Tt, p, 0, T.LOWER_SORTING_NETWORK)
+    cir, o = cc.dense_layer(d, W, Tt, comparator="sort")
+    assert nw == cir.n_wires and len(gates) == len(cir.gates)
+    assert canonical(gates, [(int(r["wire"]), int(r["value"])) for r in outs], nw, d) == \
+        canonical(cir.gate_array(), oracle_outs(o), cir.n_wires, d)
+    assert set(np.unique(gates["op"])) <= {T.AND, T.OR}
+    with pytest.raises(T.TfheError):
+        T.bnn_dense_lower_opts(d, W, Tt, p, 0, T.LOWER_SORTING_NETWORK | T.LOWER_PLUS_ONE)
 
 
 def test_conv_lowering_is_the_oracle_circuit():
