@@ -31,3 +31,10 @@ def toy_keys(orc):
     """Small parameters at which the index-by-index product definition is affordable."""
     P = orc.Params(16, 64, 1, 2, 10, 8, 2, -15, -25)
     return orc.Keys(P, 4242)
+
+
+def pytest_runtest_logstart(nodeid, location):
+    """One unbuffered line per test: long GPU tests must not look like a hung run to whoever
+    watches the output through a pipe."""
+    sys.stderr.write(f"[start] {nodeid}\n")
+    sys.stderr.flush()

@@ -11,6 +11,7 @@ Three kinds of evidence, strongest first:
 import hashlib
 import json
 import os
+import sys
 
 import numpy as np
 import pytest
@@ -102,8 +103,14 @@ def test_cfg4_conv_layer(gpu, golden):
     c = workloads.cfg4()
     x = T.to_device(T.tfhe_encrypt(sk, c["enc_seed"], c["x"].reshape(-1)))
     out = torch.empty((32 * 28 * 28, 501), dtype=torch.int32, device="cuda")
-    T.bnn_conv_encrypted(ck, x, 16, 28, 28, c["K"], c["T"], 1, 1, out)
-    torch.cuda.synchronize()
+    # four calls of 8 output channels each (units are independent, so the circuits are the same
+    # as in one call); a progress line after each keeps a watching pipe alive
+    for part in range(4):
+        ch = slice(8 * part, 8 * part + 8)
+        T.bnn_conv_encrypted(ck, x, 16, 28, 28, c["K"][ch], c["T"][ch], 1, 1, out[8 * part * 784:(8 * part + 8) * 784])
+        torch.cuda.synchronize()
+        sys.stderr.write(f"[cfg4] output channels {8 * part}..{8 * part + 7} done\n")
+        sys.stderr.flush()
     got = T.to_host(out)
     plain = cc.conv_plain(c["x"], c["K"], c["T"], 1, 1)
     assert np.array_equal(T.tfhe_decrypt(sk, got).reshape(32, 28, 28), plain)
