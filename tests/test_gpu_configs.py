@@ -97,7 +97,7 @@ def test_cfg3_dense_layer(gpu, golden, real_keys):
     assert np.array_equal(work[2 * k:], take(sel["out"]))
 
 
-def test_cfg4_conv_layer(gpu, golden):
+def test_cfg4_conv_layer(gpu, golden, capsys):
     import torch
     T, sk, ck = gpu
     c = workloads.cfg4()
@@ -109,8 +109,9 @@ def test_cfg4_conv_layer(gpu, golden):
         ch = slice(8 * part, 8 * part + 8)
         T.bnn_conv_encrypted(ck, x, 16, 28, 28, c["K"][ch], c["T"][ch], 1, 1, out[8 * part * 784:(8 * part + 8) * 784])
         torch.cuda.synchronize()
-        sys.stderr.write(f"[cfg4] output channels {8 * part}..{8 * part + 7} done\n")
-        sys.stderr.flush()
+        with capsys.disabled():
+            sys.stderr.write(f"[cfg4] output channels {8 * part}..{8 * part + 7} done\n")
+            sys.stderr.flush()
     got = T.to_host(out)
     plain = cc.conv_plain(c["x"], c["K"], c["T"], 1, 1)
     assert np.array_equal(T.tfhe_decrypt(sk, got).reshape(32, 28, 28), plain)
