@@ -9,6 +9,7 @@ measured with HIP events on the stream it runs on) and the CPU oracle timed on a
 of the same gate stream.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3|cfg2|flat] [--no-cpu]
+                  [--comparator folded|mux|sort] [--plus-one] [--share] [--copy-calibration-mib M]
 """
 import argparse
 import json
@@ -51,7 +52,8 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only; --gpus must be 1 "
-                 "(sharding across GPUs is described in DESIGN.md, not built)")
+                 "(units of a layer would be partitioned across GPUs with one all-gather of the "
+                 "output ciphertexts per layer; that is not built)")
 
     import torch
     import paper_1806_03461_amd as T
