@@ -23,8 +23,9 @@
  *     Ciphertext buffers are always owned by the caller.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     Server-side calls enqueue work on it and return without synchronising the
- *     device; host arrays they take (gate records, weights, thresholds) are
- *     consumed before the call returns.
+ *     device (except when an internal workspace has to grow, which reallocates);
+ *     host arrays they take (gate records, weights, thresholds) are consumed
+ *     before the call returns.
  *   - Key objects are opaque, owned by the library, released by tfhe_free_*.
  *     A cloud key carries device workspaces: at most one server-side call may be
  *     in flight per cloud key.

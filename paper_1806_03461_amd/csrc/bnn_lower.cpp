@@ -419,9 +419,12 @@ int evaluate(tfhe_cloud_key *ck, Builder &b, const std::vector<tfhe_out_ref> &ou
     if (int rc = tfhe::launch_fill_trivial(wires + (size_t)n_inputs * words, words, 0, stream)) return rc;
     if (int rc = tfhe::launch_fill_trivial(wires + (size_t)(n_inputs + 1) * words, words, 1, stream)) return rc;
     if (int rc = tfhe::run_gate_stream(ck, b.gates().data(), b.gates().size(), wires, nwires, stream)) return rc;
-    TFHE_HIP(hipMemcpyAsync(ck->ws_outs.ptr, outs.data(), outs.size() * sizeof(tfhe_out_ref),
+    // the output references go through pinned staging as well: no host wait
+    if (int rc = ck->stage_outs.reserve(std::max<size_t>(1, outs.size()) * sizeof(tfhe_out_ref))) return rc;
+    if (!outs.empty()) memcpy(ck->stage_outs.ptr, outs.data(), outs.size() * sizeof(tfhe_out_ref));
+    TFHE_HIP(hipMemcpyAsync(ck->ws_outs.ptr, ck->stage_outs.ptr, outs.size() * sizeof(tfhe_out_ref),
                             hipMemcpyHostToDevice, stream));
-    TFHE_HIP(hipStreamSynchronize(stream));   // `outs` is a host temporary of the caller
+    if (int rc = ck->stage_outs.mark(stream)) return rc;
     return tfhe::launch_gather_outputs(wires, (const tfhe_out_ref *)ck->ws_outs.ptr, out, outs.size(), words, stream);
 }
 

@@ -37,6 +37,19 @@ struct DeviceBuffer {
     void release();
 };
 
+// A grow-only pinned host buffer for uploads that must not block: the copy engine reads it
+// after the call returned; `busy` is recorded after each upload and waited for (host side,
+// only until that copy is done) before the buffer is written again.
+struct StagingBuffer {
+    void *ptr = nullptr;
+    size_t bytes = 0;
+    hipEvent_t busy = nullptr;
+    bool pending = false;
+    int reserve(size_t want);     // also waits for a pending upload
+    int mark(hipStream_t stream); // record `busy` after an upload was enqueued
+    void release();
+};
+
 struct TimedLaunch {
     hipEvent_t start, stop;
     int kind;   // 0 = blind rotation, 1 = key switch
@@ -63,6 +76,7 @@ struct tfhe_cloud_key {
     double2 *d_bk_fft = nullptr;    // [n][2l][4][N/2]: output o = 2*component + limb
     double2 *d_tables = nullptr;    // twiddle tables
     tfhe::DeviceBuffer ws_gates, ws_ext, ws_wires, ws_outs;
+    tfhe::StagingBuffer stage_gates, stage_outs;
     // measurement
     bool profile = false;
     std::vector<tfhe::TimedLaunch> timed;

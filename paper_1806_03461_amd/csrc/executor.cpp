@@ -37,6 +37,34 @@ void DeviceBuffer::release() {
     bytes = 0;
 }
 
+int StagingBuffer::reserve(size_t want) {
+    if (pending) { TFHE_HIP(hipEventSynchronize(busy)); pending = false; }
+    if (want <= bytes) return TFHE_OK;
+    if (ptr) { TFHE_HIP(hipHostFree(ptr)); ptr = nullptr; bytes = 0; }
+    const size_t grown = std::max(want, bytes + bytes / 2);
+    hipError_t e = hipHostMalloc(&ptr, grown, hipHostMallocDefault);
+    if (e != hipSuccess) {
+        ptr = nullptr;
+        return set_error(TFHE_E_ALLOC, "hipHostMalloc of %zu bytes failed: %s", grown, hipGetErrorString(e));
+    }
+    bytes = grown;
+    return TFHE_OK;
+}
+
+int StagingBuffer::mark(hipStream_t stream) {
+    if (!busy) TFHE_HIP(hipEventCreateWithFlags(&busy, hipEventDisableTiming));
+    TFHE_HIP(hipEventRecord(busy, stream));
+    pending = true;
+    return TFHE_OK;
+}
+
+void StagingBuffer::release() {
+    if (pending) (void)hipEventSynchronize(busy);
+    if (busy) (void)hipEventDestroy(busy);
+    if (ptr) (void)hipHostFree(ptr);
+    ptr = nullptr; bytes = 0; busy = nullptr; pending = false;
+}
+
 namespace {
 
 constexpr size_t kChunkGates = 32768;   // gates per kernel pair; bounds the extract workspace (134 MB)
@@ -180,7 +208,10 @@ int run_gate_stream(tfhe_cloud_key *ck, const tfhe_gate_rec *gates, size_t ngate
     std::vector<size_t> start(max_level + 2, 0);
     for (size_t g = 0; g < ngates; ++g) ++start[level[g] + 1];
     for (int32_t l = 1; l <= max_level + 1; ++l) start[l] += start[l - 1];
-    std::vector<tfhe_gate_rec> sorted(ngates);
+    // sorted records go through a pinned staging buffer: the upload is ordered on the stream and
+    // the call does not wait for it (nor for anything queued before it)
+    if (int rc = ck->stage_gates.reserve(ngates * sizeof(tfhe_gate_rec))) return rc;
+    tfhe_gate_rec *sorted = (tfhe_gate_rec *)ck->stage_gates.ptr;
     {
         std::vector<size_t> at(start.begin(), start.end());
         for (size_t g = 0; g < ngates; ++g) sorted[at[level[g]]++] = gates[g];
@@ -188,10 +219,9 @@ int run_gate_stream(tfhe_cloud_key *ck, const tfhe_gate_rec *gates, size_t ngate
     if (int rc = ck->ws_gates.reserve(ngates * sizeof(tfhe_gate_rec))) return rc;
     const size_t biggest = std::min(kChunkGates, ngates);
     if (int rc = ck->ws_ext.reserve(biggest * (size_t)(ck->params.N + 1) * sizeof(uint32_t))) return rc;
-    // synchronous with respect to the host buffer, ordered on the stream
-    TFHE_HIP(hipMemcpyAsync(ck->ws_gates.ptr, sorted.data(), ngates * sizeof(tfhe_gate_rec),
-                            hipMemcpyHostToDevice, stream));
-    TFHE_HIP(hipStreamSynchronize(stream));
+    TFHE_HIP(hipMemcpyAsync(ck->ws_gates.ptr, sorted, ngates * sizeof(tfhe_gate_rec), hipMemcpyHostToDevice,
+                            stream));
+    if (int rc = ck->stage_gates.mark(stream)) return rc;
     const tfhe_gate_rec *d_recs = (const tfhe_gate_rec *)ck->ws_gates.ptr;
     for (int32_t l = 1; l <= max_level; ++l) {
         for (size_t at = start[l]; at < start[l + 1];) {
@@ -269,6 +299,7 @@ void tfhe_free_cloud_key(tfhe_cloud_key *ck) {
     }
     for (auto &tl : ck->timed) { (void)hipEventDestroy(tl.start); (void)hipEventDestroy(tl.stop); }
     ck->ws_gates.release(); ck->ws_ext.release(); ck->ws_wires.release(); ck->ws_outs.release();
+    ck->stage_gates.release(); ck->stage_outs.release();
     ck->magic = 0;
     delete ck;
 }
