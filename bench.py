@@ -10,6 +10,10 @@ of the same gate stream.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3|cfg2|flat] [--no-cpu]
                   [--comparator folded|mux|sort] [--plus-one] [--share] [--copy-calibration-mib M]
+
+Further workloads, not the headline: whole networks in the shapes of the paper's own models
+(Sec. 5.2) on synthetic weights, a step being one encrypted inference through every layer:
+  --workload cancer | diabetes | faces [--faces-channels C]   (C = 32 is the paper's width)
 """
 import argparse
 import json
@@ -29,12 +33,30 @@ FLOPS_PER_STEP = 8 * 5 * 512 * 9 + 8 * 512 * 6 + 16 * 512 * 8
 FP64_VECTOR_PEAK_TFLOPS = 78.6
 
 
+def plain_dense(x, W, T):
+    """Popcount of agreeing (input, weight) pairs per unit; thresholded when T is given."""
+    xs = 2 * x.astype(np.int64) - 1
+    S = ((W.astype(np.int64) * xs[None, :]) > 0).sum(axis=1)
+    return S if T is None else (S >= T).astype(np.uint8)
+
+
+def plain_conv(x, K, T, stride, pad):
+    """Same per output pixel; a tap outside the image reads the bit 0."""
+    xs = np.pad(2 * x.astype(np.int64) - 1, ((0, 0), (pad, pad), (pad, pad)), constant_values=-1)
+    win = np.lib.stride_tricks.sliding_window_view(xs, K.shape[2:], axis=(1, 2))[:, ::stride, ::stride]
+    agree = (win[None] * K.astype(np.int64)[:, :, None, None] > 0)       # [O][C][Ho][Wo][kh][kw]
+    S = agree.sum(axis=(1, 4, 5))
+    return (S >= T[:, None, None]).astype(np.uint8)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=2)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--workload", default="cfg3", choices=["cfg3", "cfg2", "flat"])
+    ap.add_argument("--workload", default="cfg3", choices=["cfg3", "cfg2", "flat", "cancer", "diabetes", "faces"])
+    ap.add_argument("--faces-channels", type=int, default=2,
+                    help="output channels of the first four convolutions of --workload faces")
     ap.add_argument("--flat-count", type=int, default=65536)
     ap.add_argument("--comparator", default="folded", choices=["folded", "mux", "sort"],
                     help="threshold circuit: AND/OR chain folded by the plaintext bits (default) or "
@@ -76,7 +98,58 @@ def main():
         c = None
         name = f"flat: {args.flat_count} independent NAND gates"
 
-    if c is not None:
+    net = None
+    if args.workload in ("cancer", "diabetes", "faces"):
+        flags = {"folded": T.LOWER_DEFAULT, "mux": T.LOWER_MUX_COMPARATOR,
+                 "sort": T.LOWER_SORTING_NETWORK}[args.comparator]
+        flags |= (T.LOWER_PLUS_ONE if args.plus_one else 0) | (T.LOWER_SHARE_GATES if args.share else 0)
+        if args.workload == "faces":
+            net = workloads.paper_faces(channels=args.faces_channels)
+            name = (f"faces-shaped network: 5 convolutions 10x10 on 50x50, {args.faces_channels} channels "
+                    f"(paper: 32), then FC 25->1")
+            layers = [("conv", l) for l in net["convs"]] + [("dense", net["dense"])]
+        else:
+            net = workloads.paper_cancer() if args.workload == "cancer" else workloads.paper_diabetes()
+            name = {"cancer": "cancer-shaped network: FC 90->1",
+                    "diabetes": "diabetes-shaped network: FC 1704->10, sign, FC 10->3"}[args.workload]
+            layers = [("dense", l) for l in net["layers"]]
+        name += "".join(t for t, on in ((", Algorithm-1 MUX comparator", args.comparator == "mux"),
+                                        (", sorting network", args.comparator == "sort"),
+                                        (", '+1' trick", args.plus_one), (", shared gates", args.share)) if on)
+        x = T.to_device(T.tfhe_encrypt(sk, net["enc_seed"], net["x"].reshape(-1)))
+        plan, shape, plain, gates_per_step, gates_host = [], net["x"].shape, net["x"], 0, None
+        for li, (kind, l) in enumerate(layers):
+            last = l["T"] is None
+            if kind == "conv":
+                C_, H, Wd = shape
+                O, _, kh, kw = l["K"].shape
+                g, _, _ = T.bnn_conv_lower_opts(C_, H, Wd, l["K"], l["T"], l["stride"], l["pad"], flags)
+                plain = plain_conv(plain, l["K"], l["T"], l["stride"], l["pad"])
+                shape = plain.shape
+                buf = torch.empty((plain.size, words), dtype=torch.int32, device="cuda")
+                plan.append(("conv", (C_, H, Wd, l["K"], l["T"], l["stride"], l["pad"]), buf))
+            else:
+                p, d = l["W"].shape
+                ob = net["out_bits"] if last else 0
+                g, _, _ = T.bnn_dense_lower_opts(d, l["W"], l["T"], p, ob, flags)
+                plain = plain_dense(plain.reshape(-1), l["W"], l["T"])
+                shape = plain.shape
+                buf = torch.empty((p * (ob if last else 1), words), dtype=torch.int32, device="cuda")
+                plan.append(("dense", (d, l["W"], l["T"], p, ob), buf))
+            gates_per_step += int((g["op"] != T.MUX_ELSE).sum())
+            if li == 0:
+                gates_host, d_first = g, int(net["x"].size)
+        out = plan[-1][2]
+
+        def step():
+            h = x
+            for kind, a, buf in plan:
+                if kind == "conv":
+                    T.bnn_conv_encrypted_opts(ck, h, a[0], a[1], a[2], a[3], a[4], a[5], a[6], buf, flags)
+                else:
+                    T.bnn_dense_encrypted_opts(ck, h, a[0], a[1], a[2], a[3], buf, a[4], flags)
+                h = buf
+    elif c is not None:
         p, d = c["W"].shape
         x = T.to_device(T.tfhe_encrypt(sk, c["enc_seed"], c["x"]))
         out = torch.empty((p, words), dtype=torch.int32, device="cuda")
@@ -136,7 +209,12 @@ def main():
 
     # correctness of what was timed: decrypt and compare with the plain layer / truth table
     got = T.tfhe_decrypt(sk, T.to_host(out))
-    if c is not None:
+    if net is not None:
+        # the last layer emits its popcounts, least significant bit first
+        ob = net["out_bits"]
+        got = (got.reshape(-1, ob).astype(np.int64) << np.arange(ob)).sum(axis=1)
+        expect = plain.reshape(-1)
+    elif c is not None:
         xs = 2 * c["x"].astype(np.int64) - 1
         S = ((c["W"].astype(np.int64) * xs[None, :]) > 0).sum(axis=1)
         expect = (S >= c["T"]).astype(np.uint8)
@@ -171,8 +249,12 @@ def main():
         keys = orc.Keys(orc.default_params(), workloads.KEY_SEED)
         threads = min(16, os.cpu_count() or 1)
         ng = args.cpu_gates
-        if c is not None:
-            # the first ng gates of the layer's circuit are first-level gates: inputs only
+        if c is not None or net is not None:
+            # the first ng gates of the (first) layer's circuit are first-level gates: inputs only
+            if net is not None:
+                d = d_first
+                inner = np.maximum(gates_host["in0"], gates_host["in1"]) >= d + 2
+                ng = min(ng, int(inner.argmax()) if inner.any() else len(inner))
             sample = np.array(gates_host[:ng], dtype=orc.GATE_DTYPE)
             nin = d + 2
             wires = np.zeros((int(sample["out"].max()) + 1, words), np.uint32)

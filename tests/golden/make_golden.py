@@ -6,6 +6,11 @@ touches the GPU library.  Each entry stores the SHA-256 of the expected output c
 (n+1 little-endian uint32 words) and its decryption.  Takes about 15 minutes on 8 cores:
 
     python tests/golden/make_golden.py [threads]
+
+With "paper" as second argument it writes tests/golden/paper_shapes_outputs.json instead: sampled
+outputs of the networks in the shapes of the paper's own models (about 6 minutes on 8 cores):
+
+    python tests/golden/make_golden.py 8 paper
 """
 import hashlib
 import json
@@ -31,8 +36,61 @@ def digest(ct):
     return hashlib.sha256(np.ascontiguousarray(ct, dtype="<u4").tobytes()).hexdigest()
 
 
+DIABETES_L1_NEURONS = [3]
+FACES_L1_PIXELS = [(0, 0, 0), (0, 40, 40), (0, 17, 23)]
+
+
+def paper_shapes(threads):
+    keys = orc.Keys(orc.default_params(), workloads.KEY_SEED)
+    out = {"key_seed": workloads.KEY_SEED, "params": list(orc.default_params().as_tuple()), "entries": []}
+    t0 = time.time()
+
+    def record(cfg, unit, ct, plain, gates):
+        bit = int(keys.decrypt(ct)[0])
+        assert bit == int(plain), (cfg, unit, bit, plain)
+        out["entries"].append({"cfg": cfg, "unit": unit, "sha256": digest(ct), "bit": bit, "gates": gates})
+        print(cfg, unit, "bit", bit, "gates", gates, f"{time.time() - t0:.0f}s", flush=True)
+
+    # cancer shape: the whole network, one entry per score bit (least significant first)
+    c = workloads.paper_cancer()
+    L = c["layers"][0]
+    ct = keys.encrypt(c["x"], c["enc_seed"])
+    cir, outs = cc.dense_layer(90, L["W"], None, c["out_bits"])
+    res, _ = cc.eval_encrypted(keys, cir, ct, outs, threads)
+    score = int(cc.dense_plain(c["x"], L["W"], None)[0])
+    for b in range(c["out_bits"]):
+        record("cancer", [b], res[b], (score >> b) & 1, len(cir.gates))
+
+    # diabetes shape: whole first-layer neurons
+    c = workloads.paper_diabetes()
+    L = c["layers"][0]
+    ct = keys.encrypt(c["x"], c["enc_seed"])
+    plain = cc.dense_plain(c["x"], L["W"], L["T"])
+    for j in DIABETES_L1_NEURONS:
+        cir, outs = cc.dense_layer(1704, L["W"][j:j + 1], L["T"][j:j + 1])
+        res, _ = cc.eval_encrypted(keys, cir, ct, outs, threads)
+        record("diabetes", [0, j], res[0], plain[j], len(cir.gates))
+
+    # faces shape at one channel: pixels of the first 10x10 convolution
+    c = workloads.paper_faces(channels=1)
+    L = c["convs"][0]
+    ct = keys.encrypt(c["x"].reshape(-1), c["enc_seed"])
+    plain = cc.conv_plain(c["x"], L["K"], L["T"], 1, 0)
+    for (o, y, x) in FACES_L1_PIXELS:
+        cir, outs = cc.conv_layer(1, 50, 50, L["K"], L["T"], 1, 0, pixels=[(o, y, x)])
+        res, _ = cc.eval_encrypted(keys, cir, ct, outs, threads)
+        record("faces1", [0, o, y, x], res[0], plain[o, y, x], len(cir.gates))
+
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_shapes_outputs.json")
+    with open(path, "w") as f:
+        json.dump(out, f, indent=1)
+    print("wrote", path)
+
+
 def main():
     threads = int(sys.argv[1]) if len(sys.argv) > 1 else (os.cpu_count() or 1)
+    if len(sys.argv) > 2 and sys.argv[2] == "paper":
+        return paper_shapes(threads)
     keys = orc.Keys(orc.default_params(), workloads.KEY_SEED)
     out = {"key_seed": workloads.KEY_SEED, "params": list(orc.default_params().as_tuple()), "entries": []}
 

@@ -209,6 +209,34 @@ def test_conv_lowering_is_the_oracle_circuit():
         canonical(cir.gate_array(), oracle_outs(o), cir.n_wires, 40)
 
 
+def test_paper_shaped_networks_lower_to_the_oracle_circuits():
+    """Cancer FC 90->1, the two Diabetes layers (one neuron of the wide one), and the 10x10
+    convolution of the Faces shape on a 12x12 corner of its image."""
+    c = workloads.paper_cancer()
+    gates, outs, nw = T.bnn_dense_lower(90, c["layers"][0]["W"], None, 1, c["out_bits"])
+    cir, o = cc.dense_layer(90, c["layers"][0]["W"], None, c["out_bits"])
+    assert len(gates) == len(cir.gates) == 585 and len(outs) == 7
+    assert canonical(gates, [(int(r["wire"]), int(r["value"])) for r in outs], nw, 90) == \
+        canonical(cir.gate_array(), oracle_outs(o), cir.n_wires, 90)
+    c = workloads.paper_diabetes()
+    for L, d, rows, ob in ((c["layers"][0], 1704, slice(3, 4), 0), (c["layers"][1], 10, slice(0, 3), c["out_bits"])):
+        W, Tt = L["W"][rows], None if L["T"] is None else L["T"][rows]
+        gates, outs, nw = T.bnn_dense_lower(d, W, Tt, W.shape[0], ob)
+        cir, o = cc.dense_layer(d, W, Tt, ob)
+        assert len(gates) == len(cir.gates)
+        assert canonical(gates, [(int(r["wire"]), int(r["value"])) for r in outs], nw, d) == \
+            canonical(cir.gate_array(), oracle_outs(o), cir.n_wires, d)
+    f = workloads.paper_faces(channels=2)
+    assert [k["K"].shape for k in f["convs"]] == [(2, 1, 10, 10), (2, 2, 10, 10), (2, 2, 10, 10), (2, 2, 10, 10),
+                                                  (1, 2, 10, 10)] and f["dense"]["W"].shape == (1, 25)
+    L = f["convs"][1]
+    gates, outs, nw = T.bnn_conv_lower(2, 12, 12, L["K"], L["T"], 1, 0)
+    cir, o = cc.conv_layer(2, 12, 12, L["K"], L["T"], 1, 0)
+    assert len(outs) == 2 * 3 * 3 and len(gates) == len(cir.gates)
+    assert canonical(gates, [(int(r["wire"]), int(r["value"])) for r in outs], nw, 288) == \
+        canonical(cir.gate_array(), oracle_outs(o), cir.n_wires, 288)
+
+
 def test_benchmark_layer_lowering_counts():
     c3 = workloads.cfg3()
     gates, outs, nw = T.bnn_dense_lower(784, c3["W"], c3["T"], 512)

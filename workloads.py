@@ -1,4 +1,5 @@
-"""Seeded synthetic inputs for the five benchmark configurations.
+"""Seeded synthetic inputs: the five benchmark configurations, and whole networks in the
+shapes of the paper's own models.
 
 This module holds no arithmetic of the method: it only draws bits, weights and
 thresholds with numpy's seeded generator.  The oracle-side tests and the GPU-side
@@ -78,3 +79,57 @@ def cfg5(sizes=(784, 256, 256, 10)):
             T = None
         layers.append({"W": W, "T": T})
     return {"x": x, "layers": layers, "out_bits": 10, "enc_seed": seed_of(5) * 3 + 1}
+
+
+# ---- networks in the shapes of the paper's own models (Sec. 5.2) ------------------------------
+# Only the shapes are the paper's; inputs, weights and thresholds are drawn here.  A hidden
+# layer's batch normalisation and sign are one integer threshold per unit, drawn uniformly in
+# [ceil(0.4 m), floor(0.6 m)] for fan-in m; a network's last layer has no threshold and emits
+# its popcounts (the batch normalisation after it is the client's affine map on the decrypted
+# scores).
+
+def _thresholds(r, count, m):
+    lo, hi = int(np.ceil(0.4 * m)), int(np.floor(0.6 * m))
+    return r.integers(lo, hi + 1, count).astype(np.int32)
+
+
+def paper_cancer():
+    """One fully connected layer 90 -> 1 on a 90-bit one-hot-binned record; the score is the
+    7-bit popcount."""
+    r = _rng(11)
+    x = (r.random(90) < 1.0 / 3.0).astype(np.uint8)        # one of three bins per feature
+    W = (2 * r.integers(0, 2, (1, 90)) - 1).astype(np.int8)
+    return {"x": x, "layers": [{"W": W, "T": None}], "out_bits": 7, "enc_seed": seed_of(11) * 3 + 1}
+
+
+def paper_diabetes():
+    """Fully connected 1704 -> 10 with sign, then 10 -> 3 scores (4-bit popcounts)."""
+    r = _rng(12)
+    x = (r.random(1704) < 0.25).astype(np.uint8)
+    W1 = (2 * r.integers(0, 2, (10, 1704)) - 1).astype(np.int8)
+    W2 = (2 * r.integers(0, 2, (3, 10)) - 1).astype(np.int8)
+    return {"x": x, "layers": [{"W": W1, "T": _thresholds(r, 10, 1704)}, {"W": W2, "T": None}],
+            "out_bits": 4, "enc_seed": seed_of(12) * 3 + 1}
+
+
+def paper_faces(channels=32, size=50, window=10):
+    """Five convolutions (window x window, unit stride, no padding) on a size x size binary image,
+    `channels` output channels each but the last, which has one; then a fully connected layer on
+    the flattened map emitting one popcount score.  channels=32, size=50, window=10 is the
+    paper's shape (50 -> 41 -> 32 -> 23 -> 14 -> 5, then 25 -> 1); smaller values give the same
+    structure at a cost a test can afford.  Every convolution is followed by a threshold here
+    (the paper leaves the fifth without activation, which would feed integers, not bits, to
+    the last layer)."""
+    r = _rng(13)
+    x = (r.random((1, size, size)) < 0.5).astype(np.uint8)
+    convs, cin, side = [], 1, size
+    for li in range(5):
+        cout = channels if li < 4 else 1
+        K = (2 * r.integers(0, 2, (cout, cin, window, window)) - 1).astype(np.int8)
+        convs.append({"K": K, "T": _thresholds(r, cout, cin * window * window), "stride": 1, "pad": 0})
+        cin, side = cout, side - window + 1
+        assert side >= 1, "image too small for five windows"
+    d = cin * side * side
+    W = (2 * r.integers(0, 2, (1, d)) - 1).astype(np.int8)
+    return {"x": x, "convs": convs, "dense": {"W": W, "T": None}, "out_bits": max(1, int(d).bit_length()),
+            "enc_seed": seed_of(13) * 3 + 1}
