@@ -14,6 +14,8 @@
 // makes this cheaper than any 32-bit-integer number-theoretic transform on its VALU.
 #include <hip/hip_runtime.h>
 
+#include <cstdlib>
+
 #include "common.h"
 #include "fft512.h"
 #include "kernels.h"
@@ -138,8 +140,13 @@ __device__ __forceinline__ double2 load_key(__amdgpu_buffer_rsrc_t rsrc, uint32_
     return out;
 }
 
-template <int B, bool MARGIN>
-__global__ __launch_bounds__(kThreadsPerGate *B) __attribute__((amdgpu_waves_per_eu(3, 3))) void blind_rotate_kernel(BlindRotateArgs a) {
+// AHEAD: how many of the step's key-load parts (a part = 8 values = 32 registers; a step of a
+// one-gate workgroup has 4) are loaded for step i + 1 as soon as the products of step i are
+// done, so that their latency hides behind the inverse transforms, the rotation and the
+// forward transforms.  All of them only for launches that leave one workgroup per CU; at full
+// occupancy other workgroups already cover that latency (one part ahead: no measurable gain).
+template <int B, bool MARGIN, int AHEAD>
+__device__ __forceinline__ void blind_rotate_body(const BlindRotateArgs &a) {
     extern __shared__ __align__(16) unsigned char lds_raw[];
     GateLds *lds = reinterpret_cast<GateLds *>(lds_raw);
 
@@ -210,6 +217,23 @@ __global__ __launch_bounds__(kThreadsPerGate *B) __attribute__((amdgpu_waves_per
     const int drsh = 32 - a.bgbit;
     double worst = 0.0;
 
+    constexpr int kSlotsPerThread = (kHalf + kThreadsPerGate * B - 1) / (kThreadsPerGate * B);
+    static_assert(AHEAD >= 0 && AHEAD <= 2 * kSlotsPerThread, "parts of one step");
+    double2 ahead[AHEAD ? AHEAD : 1][4][2];     // [part = 2 * pass + half][row][output]
+    auto load_ahead = [&](int row) {
+        const uint32_t row_bytes = (uint32_t)row * 16u * kHalf * (uint32_t)sizeof(double2);
+#pragma unroll
+        for (int part = 0; part < AHEAD; ++part)
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+#pragma unroll
+                for (int o = 0; o < 2; ++o)
+                    ahead[part][r][o] = load_key(
+                        key_rsrc, (uint32_t)(tid + (part >> 1) * kThreadsPerGate * B) * (uint32_t)sizeof(double2),
+                        row_bytes + (uint32_t)((r * 4 + 2 * (part & 1) + o) * kHalf * sizeof(double2)));
+    };
+    if (AHEAD) load_ahead(0);
+
     for (int i = 0; i < a.n; ++i) {
         // ---- rotate, subtract, decompose, fold and twist ----
         const int abar = my.bar[i];
@@ -237,7 +261,6 @@ __global__ __launch_bounds__(kThreadsPerGate *B) __attribute__((amdgpu_waves_per
         {
             // key row i through a buffer descriptor: scalar base and row offset, 32-bit lane offset
             const uint32_t row_bytes = (uint32_t)i * 16u * kHalf * (uint32_t)sizeof(double2);
-            constexpr int kSlotsPerThread = (kHalf + kThreadsPerGate * B - 1) / (kThreadsPerGate * B);
 #pragma unroll
             for (int pass = 0; pass < kSlotsPerThread; ++pass) {
                 const int s = tid + pass * kThreadsPerGate * B;
@@ -256,8 +279,10 @@ __global__ __launch_bounds__(kThreadsPerGate *B) __attribute__((amdgpu_waves_per
                     for (int r = 0; r < 4; ++r)
 #pragma unroll
                         for (int o = 0; o < 2; ++o)
-                            k[r][o] = load_key(key_rsrc, voff,
-                                               row_bytes + (uint32_t)((r * 4 + 2 * half + o) * kHalf * sizeof(double2)));
+                            k[r][o] = 2 * pass + half < AHEAD
+                                          ? ahead[2 * pass + half < AHEAD ? 2 * pass + half : 0][r][o]
+                                          : load_key(key_rsrc, voff, row_bytes + (uint32_t)((r * 4 + 2 * half + o) *
+                                                                                                 kHalf * sizeof(double2)));
 #pragma unroll
                     for (int q = 0; q < B; ++q)
 #pragma unroll
@@ -279,6 +304,7 @@ __global__ __launch_bounds__(kThreadsPerGate *B) __attribute__((amdgpu_waves_per
             }
         }
         __syncthreads();
+        if (AHEAD) load_ahead(i + 1 < a.n ? i + 1 : i);
 
         // ---- inverse transform, exact rounding, accumulate ----
         inverse_from_slots(x, ln, my.spec[wv], L);
@@ -309,6 +335,17 @@ __global__ __launch_bounds__(kThreadsPerGate *B) __attribute__((amdgpu_waves_per
         atomicMax(reinterpret_cast<unsigned long long *>(a.margin),
                   (unsigned long long)__double_as_longlong(worst));
     }
+}
+
+template <int B, bool MARGIN>
+__global__ __launch_bounds__(kThreadsPerGate *B) __attribute__((amdgpu_waves_per_eu(3, 3))) void blind_rotate_kernel(BlindRotateArgs a) {
+    blind_rotate_body<B, MARGIN, 0>(a);
+}
+
+// The same step for batches of at most one gate per CU, where a gate's latency is all that counts.
+template <bool MARGIN>
+__global__ __launch_bounds__(kThreadsPerGate) __attribute__((amdgpu_waves_per_eu(1, 1))) void blind_rotate_latency_kernel(BlindRotateArgs a) {
+    blind_rotate_body<1, MARGIN, 4>(a);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -508,6 +545,21 @@ __global__ void fill_trivial_kernel(uint32_t *ct, int words, uint32_t body) {
 
 }  // namespace
 
+// Largest batch that goes to the latency variant: one gate per compute unit of the device.
+static int latency_batch_limit() {
+    static int limit = -1;
+    if (limit < 0) {
+        const char *e = getenv("TFHE_LATENCY_BATCH");
+        int dev = 0, cus = 0;
+        if (e) limit = atoi(e);
+        else if (hipGetDevice(&dev) == hipSuccess &&
+                 hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess)
+            limit = cus;
+        else limit = 0;
+    }
+    return limit;
+}
+
 size_t blind_rotate_lds_bytes(int gates_per_group) { return sizeof(GateLds) * (size_t)gates_per_group; }
 
 int launch_bk_to_spectrum(const uint32_t *bk_raw, double2 *bk_fft, const double2 *tables, int n,
@@ -538,8 +590,28 @@ static int launch_br(const BlindRotateArgs &a, hipStream_t stream) {
     return TFHE_OK;
 }
 
+// Batches that leave at most one gate per CU: the variant that loads each key row a step ahead.
+static int launch_br_latency(const BlindRotateArgs &a, hipStream_t stream) {
+    const size_t lds = blind_rotate_lds_bytes(1);
+    static bool configured = false;
+    if (!configured) {
+        TFHE_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&blind_rotate_latency_kernel<false>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        TFHE_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&blind_rotate_latency_kernel<true>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        configured = true;
+    }
+    if (a.margin)
+        hipLaunchKernelGGL(blind_rotate_latency_kernel<true>, dim3((unsigned)a.count), dim3(kThreadsPerGate), lds, stream, a);
+    else
+        hipLaunchKernelGGL(blind_rotate_latency_kernel<false>, dim3((unsigned)a.count), dim3(kThreadsPerGate), lds, stream, a);
+    TFHE_HIP(hipGetLastError());
+    return TFHE_OK;
+}
+
 int launch_blind_rotate(const BlindRotateArgs &a, int gates_per_group, hipStream_t stream) {
     if (a.count == 0) return TFHE_OK;
+    if (gates_per_group == 1 && a.count <= (size_t)latency_batch_limit()) return launch_br_latency(a, stream);
     switch (gates_per_group) {
     case 1: return launch_br<1>(a, stream);
     case 2: return launch_br<2>(a, stream);
