@@ -73,6 +73,7 @@ struct tfhe_cloud_key {
     bool uploaded = false;
     int device = -1;
     uint32_t *d_ksk = nullptr;
+    void *d_ksk_tiles = nullptr;    // the same key as int8 operand tiles (t = 8, basebit = 2, n < 512 only)
     double2 *d_bk_fft = nullptr;    // [n][2l][4][N/2]: output o = 2*component + limb
     double2 *d_tables = nullptr;    // twiddle tables
     tfhe::DeviceBuffer ws_gates, ws_ext, ws_wires, ws_outs;

@@ -93,6 +93,18 @@ int key_switch_group(size_t count) {
     return 1;
 }
 
+// Batches from which the key switch runs as an int8 contraction on the matrix cores.  That
+// kernel takes 0.5-0.7 ms for anything up to 8,192 gates (1,024 dependent steps per workgroup);
+// the gather kernels are faster below about 400 gates.
+int key_switch_matrix(size_t count) {
+    static long threshold = -1;
+    if (threshold < 0) {
+        const char *e = getenv("TFHE_KS_MATRIX_FROM");
+        threshold = e ? atol(e) : 512;
+    }
+    return threshold > 0 && count >= (size_t)threshold;
+}
+
 int check_cloud_key(const tfhe_cloud_key *ck) {
     if (!ck) return set_error(TFHE_E_NULL, "cloud key is NULL");
     if (ck->magic != TFHE_CK_MAGIC) return set_error(TFHE_E_PARAM, "not a cloud key");
@@ -129,6 +141,8 @@ int run_batch(tfhe_cloud_key *ck, const tfhe_gate_rec *d_recs, int uniform_op, c
     ks.ext = br.ext; ks.recs = d_recs; ks.out = out; ks.count = count; ks.ksk = ck->d_ksk;
     ks.n = P.n; ks.t = P.ks_t; ks.basebit = P.ks_basebit; ks.stride = (P.n + 2) & ~1;
     ks.group = key_switch_group(count);
+    ks.ksk_tiles = ck->d_ksk_tiles;
+    ks.matrix = key_switch_matrix(count);
     // few gates (the deep, narrow levels of a circuit): spread each gate over several
     // workgroups so that the whole chip works on the batch
     ks.splits = 1;
@@ -271,6 +285,11 @@ int tfhe_cloud_key_upload(tfhe_cloud_key *ck) {
     TFHE_HIP(hipMemcpy2D(ck->d_ksk, stride * sizeof(uint32_t), ck->ksk_raw.data(), row * sizeof(uint32_t),
                          row * sizeof(uint32_t), rows, hipMemcpyHostToDevice));
 
+    if (P.ks_t == 8 && P.ks_basebit == 2 && P.N == 1024 && P.n + 1 <= 512) {
+        TFHE_HIP(hipMalloc(&ck->d_ksk_tiles, ksk_tiles_bytes()));
+        if (int rc = launch_ksk_to_tiles(ck->d_ksk, (int)stride, (int)row, ck->d_ksk_tiles, nullptr)) return rc;
+    }
+
     // bootstrapping key: raw to device, transform on device, raw copy released
     uint32_t *d_raw = nullptr;
     const size_t bk_bytes = ck->bk_raw.size() * sizeof(uint32_t);
@@ -293,6 +312,7 @@ void tfhe_free_cloud_key(tfhe_cloud_key *ck) {
     if (ck->uploaded) {
         (void)hipDeviceSynchronize();
         (void)hipFree(ck->d_ksk);
+        (void)hipFree(ck->d_ksk_tiles);
         (void)hipFree(ck->d_bk_fft);
         (void)hipFree(ck->d_tables);
         (void)hipFree(ck->d_margin);

@@ -29,6 +29,8 @@ struct KeySwitchArgs {
     int splits;                  // group == 1 only: workgroups sharing one gate's mask words (power of two)
     int group;                   // gates sharing one pass over the key (1 = one gate per workgroup)
     int stride;                  // words per key row on the device: n+1 rounded up to even, pad = 0
+    const void *ksk_tiles;       // device, optional: the key as signed-byte tiles for the matrix-core kernel
+    int matrix;                  // use the matrix-core kernel (needs ksk_tiles, t = 8, basebit = 2, n + 1 <= 512)
 };
 
 size_t blind_rotate_lds_bytes(int gates_per_group);
@@ -36,6 +38,9 @@ int launch_bk_to_spectrum(const uint32_t *bk_raw, double2 *bk_fft, const double2
                           hipStream_t stream);
 int launch_blind_rotate(const BlindRotateArgs &a, int gates_per_group, hipStream_t stream);
 int launch_key_switch(const KeySwitchArgs &a, hipStream_t stream);
+// the key-switching key (device, padded rows) as int8 operand tiles; `tiles` holds ksk_tiles_bytes()
+size_t ksk_tiles_bytes();
+int launch_ksk_to_tiles(const uint32_t *ksk, int stride, int words, void *tiles, hipStream_t stream);
 // ext[e] += ext[e+1]; ext[e].body += 1/8 for every first half e of a multiplexer
 int launch_mux_combine(uint32_t *ext, const tfhe_gate_rec *recs, size_t count, hipStream_t stream);
 int launch_gather_outputs(const uint32_t *wires, const tfhe_out_ref *refs, uint32_t *out, size_t count,

@@ -510,6 +510,149 @@ __global__ __launch_bounds__(256) void key_switch_shared_kernel(KeySwitchArgs a)
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// Key switch of large batches as a dense contraction on the matrix cores (t = 8 digits in base
+// 4, N = 1024, n + 1 <= 512).  With one-hot digits the sum is a matrix product
+//     S[g][c] = sum_{i, j, v} [digit_ij(g) == v] * KSK[i][j][v][c]      (v = 0: a zero row)
+// with K = 1024 * 8 * 4 = 32,768.  The 32-bit key words are split into four balanced signed
+// bytes, x = s0 + 2^8 s1 + 2^16 s2 + 2^24 s3 (mod 2^32), |s| <= 128, so every plane is an exact
+// int8 x int8 -> int32 product (|sum| <= 2^20) and S is recombined with shifts.
+//
+// v_mfma_i32_32x32x32_i8: lane l supplies row (A) / column (B) l % 32 and the 16 bytes of
+// k-group l / 32; both operands use the same byte <-> k map, which is all the contraction needs.
+// One k-step of 32 is one mask word i: its 8 digits x 4 values.  A lane's A operand is built
+// in registers: 4 digits -> 4 words 1 << (8 * digit).  The key is pre-tiled so that a B operand
+// (32 columns x 32 k) is 1 KB contiguous in lane order: tiles[block of 32 words][i][plane][lane].
+//
+// Workgroup = 4 waves = 256 gates x 64 output words; wave = 128 gates x 32 words x 4 planes =
+// 16 accumulator tiles (256 registers): per mask word 4 B tiles are loaded and 16 MFMAs issued.
+// ------------------------------------------------------------------------------------------
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+constexpr int kKsRows = 256;      // gates per workgroup
+constexpr int kKsChunk = 128;     // mask words staged per round (132 KB of LDS: one workgroup per CU anyway)
+constexpr int kKsAhead = 8;       // mask words whose key tiles are in flight
+
+struct KsMatrixLds {
+    uint32_t mask_words[kKsChunk][kKsRows + 1];     // +1: the transposing store hits 32 banks
+    int32_t out_row[kKsRows];                        // output sample of each gate, -1: none
+};
+
+// tiles[((cb * 1024 + i) * 4 + plane) * 64 + lane] = 16 bytes: byte q is plane `plane` of
+// KSK[i][4 * (lane / 32) + q / 4][q % 4][32 * cb + lane % 32]  (value 0 and words past n: 0)
+__global__ __launch_bounds__(256) void ksk_to_tiles_kernel(const uint32_t *__restrict__ ksk, int stride, int words,
+                                                           v4i *__restrict__ tiles) {
+    const int i = blockIdx.x, cb = blockIdx.y;
+    const int plane = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int c = 32 * cb + (lane & 31);
+    uint32_t packed[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+        const int j = 4 * (lane >> 5) + (q >> 2), v = q & 3;
+        uint32_t x = (v && c < words) ? ksk[((size_t)(i * 8 + j) * 3 + (v - 1)) * stride + c] : 0u;
+        int32_t digit = 0;
+#pragma unroll
+        for (int b = 0; b <= 3; ++b) {
+            digit = (int8_t)(x & 0xFFu);
+            x = (x - (uint32_t)digit) >> 8;            // exact: the low byte is zero after the subtraction
+            if (b == plane) break;
+        }
+        packed[q >> 2] |= ((uint32_t)digit & 0xFFu) << (8 * (q & 3));
+    }
+    v4i t;
+    t.x = (int)packed[0]; t.y = (int)packed[1]; t.z = (int)packed[2]; t.w = (int)packed[3];
+    tiles[(((size_t)cb * kN + i) * 4 + plane) * 64 + lane] = t;
+}
+
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void key_switch_mfma_kernel(KeySwitchArgs a) {
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+    KsMatrixLds &lds = *reinterpret_cast<KsMatrixLds *>(lds_raw);
+    uint32_t (&mask_words)[kKsChunk][kKsRows + 1] = lds.mask_words;
+    int32_t (&out_row)[kKsRows] = lds.out_row;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int wr = wave >> 1;                                   // which 128 gates
+    const int cb = 2 * blockIdx.y + (wave & 1);                 // which 32 output words
+    const size_t g0 = (size_t)blockIdx.x * kKsRows;
+    const int words = a.n + 1;
+    {
+        const size_t gi = g0 + tid;
+        int32_t row = -1;
+        if (gi < a.count) {
+            if (a.recs) { if (a.recs[gi].op != TFHE_MUX_ELSE) row = a.recs[gi].out; }
+            else if (!a.uniform_mux) row = (int32_t)gi;
+            else if (!(gi & 1)) row = (int32_t)(gi >> 1);
+        }
+        out_row[tid] = row;
+    }
+    v16i acc[4][4];
+#pragma unroll
+    for (int rt = 0; rt < 4; ++rt)
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[rt][b][r] = 0;
+    const v4i *tiles = reinterpret_cast<const v4i *>(a.ksk_tiles) + (size_t)cb * kN * 4 * 64 + lane;
+    const uint32_t round = 1u << (31 - 16);
+    const int byte_shift = 24 - 8 * (lane >> 5);               // digits 0..3 or 4..7 of the word
+    const int my_row = wr * 128 + (lane & 31);
+
+    // key tiles of the next kKsAhead mask words, in a ring of registers
+    v4i ring[kKsAhead][4];
+#pragma unroll
+    for (int s = 0; s < kKsAhead; ++s)
+#pragma unroll
+        for (int b = 0; b < 4; ++b) ring[s][b] = tiles[((size_t)s * 4 + b) * 64];
+
+    for (int i0 = 0; i0 < kN; i0 += kKsChunk) {
+        __syncthreads();                                        // the previous chunk has been consumed
+        // 32 lanes read 32 consecutive mask words of one gate; a dead gate stages all-zero digits
+        for (int idx = tid; idx < kKsChunk * kKsRows; idx += 256) {
+            const int g = idx / kKsChunk, ii = idx % kKsChunk;
+            mask_words[ii][g] = out_row[g] >= 0 ? a.ext[(g0 + g) * (size_t)(kN + 1) + i0 + ii] + round : 0u;
+        }
+        __syncthreads();
+        for (int i1 = 0; i1 < kKsChunk; i1 += kKsAhead) {
+#pragma unroll
+            for (int s = 0; s < kKsAhead; ++s) {
+                const int ii = i1 + s;
+#pragma unroll
+                for (int rt = 0; rt < 4; ++rt) {
+                    const uint32_t w = (mask_words[ii][my_row + 32 * rt] >> byte_shift) & 0xFFu;
+                    v4i at;
+                    at.x = (int)(1u << (((w >> 6) & 3u) << 3));
+                    at.y = (int)(1u << (((w >> 4) & 3u) << 3));
+                    at.z = (int)(1u << (((w >> 2) & 3u) << 3));
+                    at.w = (int)(1u << ((w & 3u) << 3));
+#pragma unroll
+                    for (int b = 0; b < 4; ++b)
+                        acc[rt][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(at, ring[s][b], acc[rt][b], 0, 0, 0);
+                }
+                // refill the slot with the tiles kKsAhead mask words on (the last ones reload the end)
+                const int nxt = i0 + ii + kKsAhead < kN ? i0 + ii + kKsAhead : kN - 1;
+#pragma unroll
+                for (int b = 0; b < 4; ++b) ring[s][b] = tiles[((size_t)nxt * 4 + b) * 64];
+            }
+        }
+    }
+    // accumulator register r of lane l: row 8 (r / 4) + 4 (l / 32) + r % 4, column l % 32
+    const int c = 32 * cb + (lane & 31);
+    if (c < words) {
+#pragma unroll
+        for (int rt = 0; rt < 4; ++rt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int g = wr * 128 + 32 * rt + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                const int32_t row = out_row[g];
+                if (row < 0) continue;
+                const uint32_t sum = (uint32_t)acc[rt][0][r] + ((uint32_t)acc[rt][1][r] << 8) +
+                                     ((uint32_t)acc[rt][2][r] << 16) + ((uint32_t)acc[rt][3][r] << 24);
+                const uint32_t body = c == a.n ? a.ext[(g0 + g) * (size_t)(kN + 1) + kN] : 0u;
+                a.out[(size_t)row * words + c] = body - sum;
+            }
+    }
+}
+
 // Multiplexer: the two half results (ring-key samples of AND(s,a) and AND(NOT s,b)) are summed,
 // 1/8 is added to the body, and the sum is what the key switch of the first half consumes.
 __global__ void mux_combine_kernel(uint32_t *ext, const tfhe_gate_rec *recs, size_t count) {
@@ -620,8 +763,29 @@ int launch_blind_rotate(const BlindRotateArgs &a, int gates_per_group, hipStream
     }
 }
 
+int launch_ksk_to_tiles(const uint32_t *ksk, int stride, int words, void *tiles, hipStream_t stream) {
+    hipLaunchKernelGGL(ksk_to_tiles_kernel, dim3(kN, 16), dim3(256), 0, stream, ksk, stride, words,
+                       reinterpret_cast<v4i *>(tiles));
+    TFHE_HIP(hipGetLastError());
+    return TFHE_OK;
+}
+
+size_t ksk_tiles_bytes() { return (size_t)16 * kN * 4 * 64 * sizeof(v4i); }
+
 int launch_key_switch(const KeySwitchArgs &a, hipStream_t stream) {
     if (a.count == 0) return TFHE_OK;
+    if (a.ksk_tiles && a.matrix && a.t == 8 && a.basebit == 2 && a.n + 1 <= 512) {
+        static bool configured = false;
+        if (!configured) {
+            TFHE_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&key_switch_mfma_kernel),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(KsMatrixLds)));
+            configured = true;
+        }
+        const dim3 grid((unsigned)((a.count + kKsRows - 1) / kKsRows), 8);
+        hipLaunchKernelGGL(key_switch_mfma_kernel, grid, dim3(256), sizeof(KsMatrixLds), stream, a);
+        TFHE_HIP(hipGetLastError());
+        return TFHE_OK;
+    }
     if (a.t == 8 && a.basebit == 2 && a.n + 1 <= 512 && a.group > 1) {
         // more gates per workgroup = less key traffic per gate but fewer, longer workgroups
 #define KS_SHARED(G)                                                                                   \

@@ -250,3 +250,47 @@ def test_mux_gate_batch_and_stream(gpu, real_keys):
     for bad in (lone, other_sel, other_sel[1:]):
         with pytest.raises(T.TfheError):
             T.tfhe_gate_stream(ck, bad, wires, 6)
+
+
+def test_matrix_core_key_switch(gpu, real_keys):
+    """Batches of 512 launch items and more switch keys with the int8 matrix-core kernel: a ragged
+    batch (two full 256-gate workgroups and a tail) whole against the oracle, a multiplexer batch
+    (every second launch item writes nothing), and a gate stream whose records carry scattered
+    output wires and multiplexer pairs."""
+    import torch
+    T, sk, ck = gpu
+    rng = np.random.default_rng(23)
+    cnt = 700
+    a, b, s = (rng.integers(0, 2, cnt).astype(np.uint8) for _ in range(3))
+    cta, ctb, cts = T.tfhe_encrypt(sk, 101, a), T.tfhe_encrypt(sk, 102, b), T.tfhe_encrypt(sk, 103, s)
+    got = run_batch(T, ck, "OR", cta, ctb)
+    assert np.array_equal(got, oracle_batch(real_keys, "OR", cta, ctb))
+    # 300 multiplexers = 600 launch items
+    m = 300
+    out = torch.empty((m, 501), dtype=torch.int32, device="cuda")
+    T.tfhe_mux_batch(ck, T.to_device(cts[:m]), T.to_device(cta[:m]), T.to_device(ctb[:m]), out, m)
+    torch.cuda.synchronize()
+    got = T.to_host(out)
+    assert np.array_equal(T.tfhe_decrypt(sk, got), np.where(s[:m] == 1, a[:m], b[:m]))
+    for i in list(rng.integers(0, m, 12)) + [0, m - 1]:
+        assert np.array_equal(got[i], real_keys.mux(cts[i], cta[i], ctb[i])), i
+    # a layer of 200 small units with Algorithm 1's comparator: every level holds 600+ items, MUX pairs included
+    d, p = 6, 200
+    W = (2 * rng.integers(0, 2, (p, d)) - 1).astype(np.int8)
+    Tt = rng.integers(1, 6, p).astype(np.int32)
+    x = rng.integers(0, 2, d).astype(np.uint8)
+    ctx = T.tfhe_encrypt(sk, 104, x)
+    res = torch.empty((p, 501), dtype=torch.int32, device="cuda")
+    T.tfhe_profile_enable(ck, True)
+    T.tfhe_profile_read(ck, reset=True)
+    T.bnn_dense_encrypted_opts(ck, T.to_device(ctx), d, W, Tt, p, res, 0, T.LOWER_MUX_COMPARATOR)
+    torch.cuda.synchronize()
+    prof = T.tfhe_profile_read(ck, reset=True)
+    T.tfhe_profile_enable(ck, False)
+    assert prof["gates"] / prof["key_switch_launches"] >= 512
+    host = T.to_host(res)
+    assert np.array_equal(T.tfhe_decrypt(sk, host), cc.dense_plain(x, W, Tt))
+    for j in (0, 57, 199):
+        cir, o = cc.dense_layer(d, W[j:j + 1], Tt[j:j + 1], comparator="mux")
+        ref, _ = cc.eval_encrypted(real_keys, cir, ctx, o, threads=16)
+        assert np.array_equal(host[j], ref[0]), j
