@@ -67,7 +67,18 @@ void StagingBuffer::release() {
 
 namespace {
 
-constexpr size_t kChunkGates = 32768;   // gates per kernel pair; bounds the extract workspace (134 MB)
+// Launch items per kernel pair.  A launch ends with CUs idling until its slowest workgroup is done
+// (about one gate latency), so a circuit level should be one launch where it can; the limit only
+// bounds the extract workspace (4,100 B per item: 1.07 GB).
+size_t chunk_gates() {
+    static size_t cached = 0;
+    if (!cached) {
+        const char *e = getenv("TFHE_CHUNK_GATES");
+        const long v = e ? atol(e) : 0;
+        cached = v >= 2 ? (size_t)v & ~(size_t)1 : (size_t)1 << 18;
+    }
+    return cached;
+}
 
 int gates_per_group() {
     static int cached = 0;
@@ -231,7 +242,9 @@ int run_gate_stream(tfhe_cloud_key *ck, const tfhe_gate_rec *gates, size_t ngate
         for (size_t g = 0; g < ngates; ++g) sorted[at[level[g]]++] = gates[g];
     }
     if (int rc = ck->ws_gates.reserve(ngates * sizeof(tfhe_gate_rec))) return rc;
-    const size_t biggest = std::min(kChunkGates, ngates);
+    const size_t kChunkGates = chunk_gates();
+    size_t biggest = 0;
+    for (int32_t l = 1; l <= max_level; ++l) biggest = std::max(biggest, std::min(kChunkGates, start[l + 1] - start[l]));
     if (int rc = ck->ws_ext.reserve(biggest * (size_t)(ck->params.N + 1) * sizeof(uint32_t))) return rc;
     TFHE_HIP(hipMemcpyAsync(ck->ws_gates.ptr, sorted, ngates * sizeof(tfhe_gate_rec), hipMemcpyHostToDevice,
                             stream));
@@ -332,6 +345,7 @@ int tfhe_gate_batch(tfhe_cloud_key *ck, int op, const uint32_t *a, const uint32_
     if (count == 0) return TFHE_OK;
     if (!a || !b || !out) return set_error(TFHE_E_NULL, "NULL ciphertext buffer");
     const size_t words = (size_t)ck->params.n + 1;
+    const size_t kChunkGates = chunk_gates();
     const size_t biggest = std::min(kChunkGates, count);
     if (int rc = ck->ws_ext.reserve(biggest * (size_t)(ck->params.N + 1) * sizeof(uint32_t))) return rc;
     for (size_t at = 0; at < count; at += kChunkGates) {
@@ -349,7 +363,7 @@ int tfhe_mux_batch(tfhe_cloud_key *ck, const uint32_t *s, const uint32_t *a, con
     if (count == 0) return TFHE_OK;
     if (!s || !a || !b || !out) return set_error(TFHE_E_NULL, "NULL ciphertext buffer");
     const size_t words = (size_t)ck->params.n + 1;
-    const size_t per_batch = kChunkGates / 2;          // two launch items per multiplexer
+    const size_t per_batch = chunk_gates() / 2;        // two launch items per multiplexer
     const size_t biggest = 2 * std::min(per_batch, count);
     if (int rc = ck->ws_ext.reserve(biggest * (size_t)(ck->params.N + 1) * sizeof(uint32_t))) return rc;
     for (size_t at = 0; at < count; at += per_batch) {

@@ -237,8 +237,17 @@ __device__ __forceinline__ void blind_rotate_body(const BlindRotateArgs &a) {
     for (int i = 0; i < a.n; ++i) {
         // ---- rotate, subtract, decompose, fold and twist ----
         const int abar = my.bar[i];
-        const unsigned char *accb = reinterpret_cast<const unsigned char *>(my.acc[comp]);
+        const unsigned char *acc0 = reinterpret_cast<const unsigned char *>(my.acc[0]);
         const uint32_t base = (uint32_t)(L - abar) << 2;       // byte offset of X^abar's source, mod 8192
+        // all sixteen rotated reads are issued before any of them is consumed
+        uint32_t rot[8][2];
+#pragma unroll
+        for (int m = 0; m < 8; ++m)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const uint32_t src = base + (uint32_t)(64 * m + h * kHalf) * 4u;
+                rot[m][h] = *reinterpret_cast<const uint32_t *>(acc0 + ((src & 4092u) | ((uint32_t)comp << 12)));
+            }
         double2 x[8];
 #pragma unroll
         for (int m = 0; m < 8; ++m) {
@@ -246,11 +255,11 @@ __device__ __forceinline__ void blind_rotate_body(const BlindRotateArgs &a) {
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
                 const int j = L + 64 * m + h * kHalf;
-                const uint32_t src = (base + (uint32_t)(64 * m + h * kHalf) * 4u) & 8191u;
-                const uint32_t p = *reinterpret_cast<const uint32_t *>(accb + (src & 4095u));
-                const uint32_t neg = (uint32_t)((int32_t)(src << 19) >> 31);   // all ones past X^N
-                const uint32_t d = (p ^ neg) - (my.acc[comp][j] + neg);        // +-p - acc[j]
-                dig[h] = (int32_t)((d + doffset) << dlsh) >> drsh;
+                const uint32_t src = base + (uint32_t)(64 * m + h * kHalf) * 4u;
+                const uint32_t past = (src >> 12) & 1u;                         // source lies past X^N: negate
+                // +-p - acc[j] + doffset, with -p = (p ^ ~0) + 1
+                const uint32_t d = (rot[m][h] ^ (0u - past)) + (doffset - my.acc[comp][j]) + past;
+                dig[h] = (int32_t)(d << dlsh) >> drsh;
             }
             x[m] = make_double2((double)dig[0], (double)dig[1]);
         }
