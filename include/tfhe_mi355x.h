@@ -27,8 +27,13 @@
  *     host arrays they take (gate records, weights, thresholds) are consumed
  *     before the call returns.
  *   - Key objects are opaque, owned by the library, released by tfhe_free_*.
- *     A cloud key carries device workspaces: at most one server-side call may be
- *     in flight per cloud key.
+ *     A cloud key carries device workspaces that its calls share: issue the
+ *     server-side calls on one cloud key from one thread at a time and on one
+ *     stream (the stream orders successive calls; calls on different streams would
+ *     race on the workspaces).  An uploaded cloud key holds about 180 MB of device
+ *     memory for the keys, up to 1.07 GB for the samples between the two kernels
+ *     (4,100 B per gate of the widest launch) and, for the layer calls, one
+ *     ciphertext (4 (n+1) bytes) per gate of the layer's circuit.
  *   - The GPU path supports N = 1024, k = 1, bk_l = 2, bk_Bgbit <= 10, n <= 1024,
  *     ks_t * ks_basebit <= 24, ks_basebit <= 4; other parameters give TFHE_E_PARAM.
  */
