@@ -437,7 +437,7 @@ int bnn_dense_lower(int d, const int8_t *W, const int32_t *T, int p, int out_bit
     return bnn_dense_lower_opts(d, W, T, p, out_bits, TFHE_LOWER_DEFAULT, gates, ngates, outs, nouts, nwires);
 }
 
-int bnn_dense_lower_opts(int d, const int8_t *W, const int32_t *T, int p, int out_bits, uint32_t flags,
+static int bnn_dense_lower_opts_impl(int d, const int8_t *W, const int32_t *T, int p, int out_bits, uint32_t flags,
                          tfhe_gate_rec **gates, size_t *ngates, tfhe_out_ref **outs, size_t *nouts,
                          size_t *nwires) {
     if (!gates || !ngates || !outs || !nouts || !nwires) return set_error(TFHE_E_NULL, "NULL output pointer");
@@ -451,6 +451,12 @@ int bnn_dense_lower_opts(int d, const int8_t *W, const int32_t *T, int p, int ou
     return TFHE_OK;
 }
 
+int bnn_dense_lower_opts(int d, const int8_t *W, const int32_t *T, int p, int out_bits, uint32_t flags,
+                         tfhe_gate_rec **gates, size_t *ngates, tfhe_out_ref **outs, size_t *nouts,
+                         size_t *nwires) {
+    return tfhe::guarded([&]() -> int { return bnn_dense_lower_opts_impl(d, W, T, p, out_bits, flags, gates, ngates, outs, nouts, nwires); });
+}
+
 int bnn_conv_lower(int C, int H, int Wd, const int8_t *K, int O, int kh, int kw, int stride, int pad,
                    const int32_t *T, tfhe_gate_rec **gates, size_t *ngates, tfhe_out_ref **outs, size_t *nouts,
                    size_t *nwires) {
@@ -458,11 +464,12 @@ int bnn_conv_lower(int C, int H, int Wd, const int8_t *K, int O, int kh, int kw,
                                nouts, nwires);
 }
 
-int bnn_conv_lower_opts(int C, int H, int Wd, const int8_t *K, int O, int kh, int kw, int stride, int pad,
+static int bnn_conv_lower_opts_impl(int C, int H, int Wd, const int8_t *K, int O, int kh, int kw, int stride, int pad,
                         const int32_t *T, uint32_t flags, tfhe_gate_rec **gates, size_t *ngates,
                         tfhe_out_ref **outs, size_t *nouts, size_t *nwires) {
     if (!gates || !ngates || !outs || !nouts || !nwires) return set_error(TFHE_E_NULL, "NULL output pointer");
-    if (C < 1 || H < 1 || Wd < 1) return set_error(TFHE_E_SIZE, "bad convolution shape");
+    if (C < 1 || H < 1 || Wd < 1 || (long long)C * H * Wd > (1ll << 30))
+        return set_error(TFHE_E_SIZE, "bad convolution shape");
     Builder b(C * H * Wd, (flags & TFHE_LOWER_SHARE_GATES) != 0);
     std::vector<tfhe_out_ref> o;
     if (int rc = lower_conv(C, H, Wd, K, O, kh, kw, stride, pad, T, flags, b, o)) return rc;
@@ -472,12 +479,18 @@ int bnn_conv_lower_opts(int C, int H, int Wd, const int8_t *K, int O, int kh, in
     return TFHE_OK;
 }
 
+int bnn_conv_lower_opts(int C, int H, int Wd, const int8_t *K, int O, int kh, int kw, int stride, int pad,
+                        const int32_t *T, uint32_t flags, tfhe_gate_rec **gates, size_t *ngates,
+                        tfhe_out_ref **outs, size_t *nouts, size_t *nwires) {
+    return tfhe::guarded([&]() -> int { return bnn_conv_lower_opts_impl(C, H, Wd, K, O, kh, kw, stride, pad, T, flags, gates, ngates, outs, nouts, nwires); });
+}
+
 int bnn_dense_encrypted(tfhe_cloud_key *ck, const uint32_t *x, int d, const int8_t *W, const int32_t *T, int p,
                         uint32_t *out, int out_bits, void *stream) {
     return bnn_dense_encrypted_opts(ck, x, d, W, T, p, out, out_bits, TFHE_LOWER_DEFAULT, stream);
 }
 
-int bnn_dense_encrypted_opts(tfhe_cloud_key *ck, const uint32_t *x, int d, const int8_t *W, const int32_t *T,
+static int bnn_dense_encrypted_opts_impl(tfhe_cloud_key *ck, const uint32_t *x, int d, const int8_t *W, const int32_t *T,
                              int p, uint32_t *out, int out_bits, uint32_t flags, void *stream) {
     if (int rc = tfhe::ensure_uploaded(ck)) return rc;
     if (!x || !out) return set_error(TFHE_E_NULL, "NULL ciphertext buffer");
@@ -488,21 +501,33 @@ int bnn_dense_encrypted_opts(tfhe_cloud_key *ck, const uint32_t *x, int d, const
     return evaluate(ck, b, o, x, d, out, (hipStream_t)stream);
 }
 
+int bnn_dense_encrypted_opts(tfhe_cloud_key *ck, const uint32_t *x, int d, const int8_t *W, const int32_t *T,
+                             int p, uint32_t *out, int out_bits, uint32_t flags, void *stream) {
+    return tfhe::guarded([&]() -> int { return bnn_dense_encrypted_opts_impl(ck, x, d, W, T, p, out, out_bits, flags, stream); });
+}
+
 int bnn_conv_encrypted(tfhe_cloud_key *ck, const uint32_t *x, int C, int H, int Wd, const int8_t *K, int O,
                        int kh, int kw, int stride, int pad, const int32_t *T, uint32_t *out, void *stream) {
     return bnn_conv_encrypted_opts(ck, x, C, H, Wd, K, O, kh, kw, stride, pad, T, out, TFHE_LOWER_DEFAULT, stream);
 }
 
-int bnn_conv_encrypted_opts(tfhe_cloud_key *ck, const uint32_t *x, int C, int H, int Wd, const int8_t *K, int O,
+static int bnn_conv_encrypted_opts_impl(tfhe_cloud_key *ck, const uint32_t *x, int C, int H, int Wd, const int8_t *K, int O,
                             int kh, int kw, int stride, int pad, const int32_t *T, uint32_t *out, uint32_t flags,
                             void *stream) {
     if (int rc = tfhe::ensure_uploaded(ck)) return rc;
     if (!x || !out) return set_error(TFHE_E_NULL, "NULL ciphertext buffer");
-    if (C < 1 || H < 1 || Wd < 1) return set_error(TFHE_E_SIZE, "bad convolution shape");
+    if (C < 1 || H < 1 || Wd < 1 || (long long)C * H * Wd > (1ll << 30))
+        return set_error(TFHE_E_SIZE, "bad convolution shape");
     Builder b(C * H * Wd, (flags & TFHE_LOWER_SHARE_GATES) != 0);
     std::vector<tfhe_out_ref> o;
     if (int rc = lower_conv(C, H, Wd, K, O, kh, kw, stride, pad, T, flags, b, o)) return rc;
     return evaluate(ck, b, o, x, C * H * Wd, out, (hipStream_t)stream);
+}
+
+int bnn_conv_encrypted_opts(tfhe_cloud_key *ck, const uint32_t *x, int C, int H, int Wd, const int8_t *K, int O,
+                            int kh, int kw, int stride, int pad, const int32_t *T, uint32_t *out, uint32_t flags,
+                            void *stream) {
+    return tfhe::guarded([&]() -> int { return bnn_conv_encrypted_opts_impl(ck, x, C, H, Wd, K, O, kh, kw, stride, pad, T, out, flags, stream); });
 }
 
 }  // extern "C"

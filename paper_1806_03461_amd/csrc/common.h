@@ -3,6 +3,8 @@
 #include <cstdarg>
 #include <cstdint>
 #include <cstdio>
+#include <exception>
+#include <new>
 #include <vector>
 
 #include <hip/hip_runtime.h>
@@ -20,6 +22,20 @@ int set_error(int code, const char *fmt, ...);
             return tfhe::set_error(TFHE_E_HIP, "%s failed: %s (%s:%d)", #call,              \
                                    hipGetErrorString(e_), __FILE__, __LINE__);              \
     } while (0)
+
+// Runs an entry point's body: no C++ exception leaves the C ABI.
+template <class F>
+int guarded(F &&body) {
+    try {
+        return body();
+    } catch (const std::bad_alloc &) {
+        return set_error(TFHE_E_ALLOC, "out of host memory");
+    } catch (const std::exception &e) {
+        return set_error(TFHE_E_ALLOC, "unexpected failure: %s", e.what());
+    } catch (...) {
+        return set_error(TFHE_E_ALLOC, "unexpected failure");
+    }
+}
 
 int check_params_host(const tfhe_params *p);   // what keygen / encrypt accept
 int check_params_gpu(const tfhe_params *p);    // what the kernels accept

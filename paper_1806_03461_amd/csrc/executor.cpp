@@ -261,6 +261,17 @@ int run_gate_stream(tfhe_cloud_key *ck, const tfhe_gate_rec *gates, size_t ngate
     return TFHE_OK;
 }
 
+void release_device_keys(tfhe_cloud_key *ck) {
+    if (ck->d_ksk) (void)hipFree(ck->d_ksk);
+    if (ck->d_ksk_tiles) (void)hipFree(ck->d_ksk_tiles);
+    if (ck->d_bk_fft) (void)hipFree(ck->d_bk_fft);
+    if (ck->d_tables) (void)hipFree(ck->d_tables);
+    if (ck->d_margin) (void)hipFree(ck->d_margin);
+    ck->d_ksk = nullptr; ck->d_ksk_tiles = nullptr; ck->d_bk_fft = nullptr; ck->d_tables = nullptr;
+    ck->d_margin = nullptr;
+    ck->uploaded = false;
+}
+
 int ensure_uploaded(tfhe_cloud_key *ck) {
     if (int rc = check_cloud_key(ck)) return rc;
     if (ck->uploaded) return TFHE_OK;
@@ -273,7 +284,7 @@ using namespace tfhe;
 
 extern "C" {
 
-int tfhe_cloud_key_upload(tfhe_cloud_key *ck) {
+static int tfhe_cloud_key_upload_impl(tfhe_cloud_key *ck) {
     if (int rc = check_cloud_key(ck)) return rc;
     if (ck->uploaded) return TFHE_OK;
     const tfhe_params &P = ck->params;
@@ -281,6 +292,7 @@ int tfhe_cloud_key_upload(tfhe_cloud_key *ck) {
     TFHE_HIP(hipGetDeviceCount(&count));
     if (count < 1) return set_error(TFHE_E_HIP, "no HIP device");
     TFHE_HIP(hipGetDevice(&ck->device));
+    release_device_keys(ck);          // an earlier attempt may have failed half-way
 
     // twiddle table psi^j = exp(i pi j / 1024), j < 2048, evaluated in extended precision
     std::vector<double2> tables(2048);
@@ -304,15 +316,18 @@ int tfhe_cloud_key_upload(tfhe_cloud_key *ck) {
     }
 
     // bootstrapping key: raw to device, transform on device, raw copy released
-    uint32_t *d_raw = nullptr;
+    struct RawKey {               // released on every way out
+        DeviceBuffer buf;
+        ~RawKey() { buf.release(); }
+    } raw;
     const size_t bk_bytes = ck->bk_raw.size() * sizeof(uint32_t);
-    TFHE_HIP(hipMalloc((void **)&d_raw, bk_bytes));
-    TFHE_HIP(hipMemcpy(d_raw, ck->bk_raw.data(), bk_bytes, hipMemcpyHostToDevice));
+    if (int rc = raw.buf.reserve(bk_bytes)) return rc;
+    TFHE_HIP(hipMemcpy(raw.buf.ptr, ck->bk_raw.data(), bk_bytes, hipMemcpyHostToDevice));
     const size_t fft_words = (size_t)P.n * 16 * 512;
     TFHE_HIP(hipMalloc((void **)&ck->d_bk_fft, fft_words * sizeof(double2)));
-    if (int rc = launch_bk_to_spectrum(d_raw, ck->d_bk_fft, ck->d_tables, P.n, nullptr)) return rc;
+    if (int rc = launch_bk_to_spectrum((const uint32_t *)raw.buf.ptr, ck->d_bk_fft, ck->d_tables, P.n, nullptr))
+        return rc;
     TFHE_HIP(hipDeviceSynchronize());
-    TFHE_HIP(hipFree(d_raw));
 
     TFHE_HIP(hipMalloc((void **)&ck->d_margin, sizeof(double)));
     TFHE_HIP(hipMemset(ck->d_margin, 0, sizeof(double)));
@@ -320,16 +335,14 @@ int tfhe_cloud_key_upload(tfhe_cloud_key *ck) {
     return TFHE_OK;
 }
 
+int tfhe_cloud_key_upload(tfhe_cloud_key *ck) {
+    return tfhe::guarded([&]() -> int { return tfhe_cloud_key_upload_impl(ck); });
+}
+
 void tfhe_free_cloud_key(tfhe_cloud_key *ck) {
     if (!ck || ck->magic != TFHE_CK_MAGIC) return;
-    if (ck->uploaded) {
-        (void)hipDeviceSynchronize();
-        (void)hipFree(ck->d_ksk);
-        (void)hipFree(ck->d_ksk_tiles);
-        (void)hipFree(ck->d_bk_fft);
-        (void)hipFree(ck->d_tables);
-        (void)hipFree(ck->d_margin);
-    }
+    if (ck->uploaded) (void)hipDeviceSynchronize();
+    release_device_keys(ck);          // also what a failed upload left behind
     for (auto &tl : ck->timed) { (void)hipEventDestroy(tl.start); (void)hipEventDestroy(tl.stop); }
     ck->ws_gates.release(); ck->ws_ext.release(); ck->ws_wires.release(); ck->ws_outs.release();
     ck->stage_gates.release(); ck->stage_outs.release();
@@ -337,7 +350,7 @@ void tfhe_free_cloud_key(tfhe_cloud_key *ck) {
     delete ck;
 }
 
-int tfhe_gate_batch(tfhe_cloud_key *ck, int op, const uint32_t *a, const uint32_t *b, uint32_t *out,
+static int tfhe_gate_batch_impl(tfhe_cloud_key *ck, int op, const uint32_t *a, const uint32_t *b, uint32_t *out,
                     size_t count, void *stream) {
     if (int rc = ensure_uploaded(ck)) return rc;
     if (op < TFHE_NAND || op > TFHE_XNOR)
@@ -357,7 +370,12 @@ int tfhe_gate_batch(tfhe_cloud_key *ck, int op, const uint32_t *a, const uint32_
     return TFHE_OK;
 }
 
-int tfhe_mux_batch(tfhe_cloud_key *ck, const uint32_t *s, const uint32_t *a, const uint32_t *b, uint32_t *out,
+int tfhe_gate_batch(tfhe_cloud_key *ck, int op, const uint32_t *a, const uint32_t *b, uint32_t *out,
+                    size_t count, void *stream) {
+    return tfhe::guarded([&]() -> int { return tfhe_gate_batch_impl(ck, op, a, b, out, count, stream); });
+}
+
+static int tfhe_mux_batch_impl(tfhe_cloud_key *ck, const uint32_t *s, const uint32_t *a, const uint32_t *b, uint32_t *out,
                    size_t count, void *stream) {
     if (int rc = ensure_uploaded(ck)) return rc;
     if (count == 0) return TFHE_OK;
@@ -375,12 +393,22 @@ int tfhe_mux_batch(tfhe_cloud_key *ck, const uint32_t *s, const uint32_t *a, con
     return TFHE_OK;
 }
 
-int tfhe_gate_stream(tfhe_cloud_key *ck, const tfhe_gate_rec *gates, size_t ngates, uint32_t *wires,
+int tfhe_mux_batch(tfhe_cloud_key *ck, const uint32_t *s, const uint32_t *a, const uint32_t *b, uint32_t *out,
+                   size_t count, void *stream) {
+    return tfhe::guarded([&]() -> int { return tfhe_mux_batch_impl(ck, s, a, b, out, count, stream); });
+}
+
+static int tfhe_gate_stream_impl(tfhe_cloud_key *ck, const tfhe_gate_rec *gates, size_t ngates, uint32_t *wires,
                      size_t nwires, void *stream) {
     if (int rc = ensure_uploaded(ck)) return rc;
     if (ngates == 0) return TFHE_OK;
     if (!gates || !wires) return set_error(TFHE_E_NULL, "NULL gates or wires");
     return run_gate_stream(ck, gates, ngates, wires, nwires, (hipStream_t)stream);
+}
+
+int tfhe_gate_stream(tfhe_cloud_key *ck, const tfhe_gate_rec *gates, size_t ngates, uint32_t *wires,
+                     size_t nwires, void *stream) {
+    return tfhe::guarded([&]() -> int { return tfhe_gate_stream_impl(ck, gates, ngates, wires, nwires, stream); });
 }
 
 int tfhe_profile_enable(tfhe_cloud_key *ck, int on) {
@@ -389,7 +417,7 @@ int tfhe_profile_enable(tfhe_cloud_key *ck, int on) {
     return TFHE_OK;
 }
 
-int tfhe_profile_read(tfhe_cloud_key *ck, tfhe_profile *out, int reset) {
+static int tfhe_profile_read_impl(tfhe_cloud_key *ck, tfhe_profile *out, int reset) {
     if (int rc = check_cloud_key(ck)) return rc;
     if (!out) return set_error(TFHE_E_NULL, "NULL profile output");
     for (auto &tl : ck->timed) {
@@ -413,6 +441,10 @@ int tfhe_profile_read(tfhe_cloud_key *ck, tfhe_profile *out, int reset) {
         ck->prof_gates = 0;
     }
     return TFHE_OK;
+}
+
+int tfhe_profile_read(tfhe_cloud_key *ck, tfhe_profile *out, int reset) {
+    return tfhe::guarded([&]() -> int { return tfhe_profile_read_impl(ck, out, reset); });
 }
 
 int tfhe_rounding_margin_enable(tfhe_cloud_key *ck, int on) {

@@ -181,7 +181,7 @@ int tfhe_keygen(const tfhe_params *p, uint64_t seed, tfhe_secret_key **sk_out, t
     return TFHE_OK;
 }
 
-int tfhe_encrypt(const tfhe_secret_key *sk, uint64_t seed, const uint8_t *bits, size_t nbits,
+static int tfhe_encrypt_impl(const tfhe_secret_key *sk, uint64_t seed, const uint8_t *bits, size_t nbits,
                  uint32_t *ct) {
     if (!sk || (nbits && (!bits || !ct))) return set_error(TFHE_E_NULL, "NULL argument to tfhe_encrypt");
     if (sk->magic != TFHE_SK_MAGIC) return set_error(TFHE_E_PARAM, "not a secret key");
@@ -199,7 +199,12 @@ int tfhe_encrypt(const tfhe_secret_key *sk, uint64_t seed, const uint8_t *bits, 
     return TFHE_OK;
 }
 
-int tfhe_decrypt(const tfhe_secret_key *sk, const uint32_t *ct, size_t nbits, uint8_t *bits) {
+int tfhe_encrypt(const tfhe_secret_key *sk, uint64_t seed, const uint8_t *bits, size_t nbits,
+                 uint32_t *ct) {
+    return tfhe::guarded([&]() -> int { return tfhe_encrypt_impl(sk, seed, bits, nbits, ct); });
+}
+
+static int tfhe_decrypt_impl(const tfhe_secret_key *sk, const uint32_t *ct, size_t nbits, uint8_t *bits) {
     if (!sk || (nbits && (!bits || !ct))) return set_error(TFHE_E_NULL, "NULL argument to tfhe_decrypt");
     if (sk->magic != TFHE_SK_MAGIC) return set_error(TFHE_E_PARAM, "not a secret key");
     const int n = sk->params.n;
@@ -211,6 +216,10 @@ int tfhe_decrypt(const tfhe_secret_key *sk, const uint32_t *ct, size_t nbits, ui
         bits[s] = (int32_t)phase > 0;
     }
     return TFHE_OK;
+}
+
+int tfhe_decrypt(const tfhe_secret_key *sk, const uint32_t *ct, size_t nbits, uint8_t *bits) {
+    return tfhe::guarded([&]() -> int { return tfhe_decrypt_impl(sk, ct, nbits, bits); });
 }
 
 int tfhe_trivial(const tfhe_params *p, int bit, uint32_t *ct) {
@@ -235,7 +244,7 @@ int tfhe_get_params(const void *key, int is_cloud_key, tfhe_params *out) {
     return TFHE_OK;
 }
 
-int tfhe_export_key(const void *key, int which, void *buf, size_t *len) {
+static int tfhe_export_key_impl(const void *key, int which, void *buf, size_t *len) {
     if (!key || !len) return set_error(TFHE_E_NULL, "NULL argument to tfhe_export_key");
     const std::vector<uint32_t> *src = nullptr;
     if (which == TFHE_KEY_LWE_SK || which == TFHE_KEY_TRLWE_SK) {
@@ -255,6 +264,10 @@ int tfhe_export_key(const void *key, int which, void *buf, size_t *len) {
     memcpy(buf, src->data(), bytes);
     *len = bytes;
     return TFHE_OK;
+}
+
+int tfhe_export_key(const void *key, int which, void *buf, size_t *len) {
+    return tfhe::guarded([&]() -> int { return tfhe_export_key_impl(key, which, buf, len); });
 }
 
 void tfhe_free_secret_key(tfhe_secret_key *sk) {
