@@ -12,6 +12,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <new>
+#include <thread>
 
 #include "common.h"
 #include "kernels.h"
@@ -74,6 +75,31 @@ public:
         r.op = TFHE_MUX_ELSE; r.neg1 = (uint8_t)b.flag; r.in1 = b.wire;
         gates_.push_back(r);
         return Sig::of(r.out);
+    }
+
+    // Appending the gates of builders over the same inputs, with their gate wires renumbered,
+    // gives what emitting those gates here would have given.  grow() makes room for a part's
+    // records and wires and says where they go; place() copies the part there and renumbers its
+    // output references `part_outs` (calls for different parts may run concurrently).
+    struct Slot { size_t gate_at; int32_t wire_shift; };
+    Slot grow(const Builder &part) {
+        const Slot s{gates_.size(), next_ - (zero_ + 2)};
+        gates_.resize(gates_.size() + part.gates_.size());
+        next_ += part.next_ - (zero_ + 2);
+        return s;
+    }
+    void place(const Builder &part, std::vector<tfhe_out_ref> &part_outs, Slot s) {
+        const int32_t first = zero_ + 2;
+        tfhe_gate_rec *dst = gates_.data() + s.gate_at;
+        for (size_t g = 0; g < part.gates_.size(); ++g) {
+            tfhe_gate_rec r = part.gates_[g];
+            if (r.in0 >= first) r.in0 += s.wire_shift;
+            if (r.in1 >= first) r.in1 += s.wire_shift;
+            r.out += s.wire_shift;
+            dst[g] = r;
+        }
+        for (tfhe_out_ref &o : part_outs)
+            if (o.wire >= first) o.wire += s.wire_shift;
     }
 
     static int width_of(int64_t bound) { int w = 0; while (bound >> w) ++w; return w; }
@@ -328,6 +354,52 @@ int check_weights(const int8_t *W, size_t count) {
     return TFHE_OK;
 }
 
+// Units that share nothing are lowered by several host threads, each into a builder of its own
+// over a contiguous range of units; appending the parts in order gives exactly the records and
+// wire numbers of the serial loop.  per_unit(builder, outs, j) lowers unit j.
+template <class PerUnit>
+int lower_units(int count, size_t work_per_unit, int32_t n_inputs, Builder &b, std::vector<tfhe_out_ref> &outs,
+                PerUnit per_unit) {
+    int threads = (int)std::min<size_t>(std::min<unsigned>(16u, std::max(1u, std::thread::hardware_concurrency())),
+                                        (size_t)count);
+    if ((size_t)count * work_per_unit < 200000) threads = 1;
+    if (threads <= 1) {
+        for (int j = 0; j < count; ++j) per_unit(b, outs, j);
+        return TFHE_OK;
+    }
+    struct Part {
+        Builder b;
+        std::vector<tfhe_out_ref> outs;
+        bool failed = false;
+        explicit Part(int32_t n) : b(n) {}
+    };
+    std::vector<Part> parts;
+    parts.reserve(threads);
+    for (int t = 0; t < threads; ++t) parts.emplace_back(n_inputs);
+    std::vector<std::thread> pool;
+    for (int t = 0; t < threads; ++t)
+        pool.emplace_back([&, t]() {
+            const int lo = (int)((int64_t)count * t / threads), hi = (int)((int64_t)count * (t + 1) / threads);
+            try {
+                // about 7 gate records per input of a reduce-tree unit
+                parts[t].b.gates().reserve((size_t)(hi - lo) * work_per_unit * 7 + 64);
+                for (int j = lo; j < hi; ++j) per_unit(parts[t].b, parts[t].outs, j);
+            } catch (...) {
+                parts[t].failed = true;
+            }
+        });
+    for (std::thread &th : pool) th.join();
+    for (Part &part : parts)
+        if (part.failed) return set_error(TFHE_E_ALLOC, "out of host memory while lowering");
+    std::vector<Builder::Slot> slots;
+    for (Part &part : parts) slots.push_back(b.grow(part.b));
+    pool.clear();
+    for (int t = 0; t < threads; ++t) pool.emplace_back([&, t]() { b.place(parts[t].b, parts[t].outs, slots[t]); });
+    for (std::thread &th : pool) th.join();
+    for (Part &part : parts) outs.insert(outs.end(), part.outs.begin(), part.outs.end());
+    return TFHE_OK;
+}
+
 int lower_dense(int d, const int8_t *W, const int32_t *T, int p, int out_bits, uint32_t flags, Builder &b,
                 std::vector<tfhe_out_ref> &outs) {
     if (flags & ~(uint32_t)(TFHE_LOWER_MUX_COMPARATOR | TFHE_LOWER_PLUS_ONE | TFHE_LOWER_SHARE_GATES |
@@ -351,6 +423,10 @@ int lower_dense(int d, const int8_t *W, const int32_t *T, int p, int out_bits, u
     if (int rc = check_weights(W, (size_t)d * p)) return rc;
     std::vector<Sig> x(d);
     for (int i = 0; i < d; ++i) x[i] = Sig::of(i);
+    if (!(flags & (TFHE_LOWER_PLUS_ONE | TFHE_LOWER_SHARE_GATES)))
+        return lower_units(p, (size_t)d, d, b, outs, [&](Builder &bb, std::vector<tfhe_out_ref> &oo, int j) {
+            bb.unit(x, W + (size_t)j * d, T ? T + j : nullptr, out_bits, oo, flags);
+        });
     Number X;          // popcount of all inputs, built on first use, shared by the layer's units
     for (int j = 0; j < p; ++j) {
         const int8_t *w = W + (size_t)j * d;
@@ -379,20 +455,34 @@ int lower_conv(int C, int H, int Wd, const int8_t *K, int O, int kh, int kw, int
     const size_t taps = (size_t)C * kh * kw;
     if (int rc = check_weights(K, taps * O)) return rc;
     const int Ho = (H + 2 * pad - kh) / stride + 1, Wo = (Wd + 2 * pad - kw) / stride + 1;
+    auto gather_field = [=](std::vector<Sig> &f, int y, int x, int32_t zero_wire) {
+        size_t t = 0;
+        for (int c = 0; c < C; ++c)
+            for (int ky = 0; ky < kh; ++ky)
+                for (int kx = 0; kx < kw; ++kx, ++t) {
+                    const int iy = y * stride + ky - pad, ix = x * stride + kx - pad;
+                    const bool inside = iy >= 0 && iy < H && ix >= 0 && ix < Wd;
+                    f[t] = Sig::of(inside ? (c * H + iy) * Wd + ix : zero_wire);
+                }
+    };
+    if (!(flags & (TFHE_LOWER_PLUS_ONE | TFHE_LOWER_SHARE_GATES))) {
+        if ((long long)O * Ho * Wo > INT32_MAX) return set_error(TFHE_E_SIZE, "too many output pixels");
+        return lower_units(O * Ho * Wo, taps, C * H * Wd, b, outs,
+                           [&](Builder &bb, std::vector<tfhe_out_ref> &oo, int u) {
+                               thread_local std::vector<Sig> f;
+                               f.resize(taps);
+                               const int o = u / (Ho * Wo), y = u / Wo % Ho, x = u % Wo;
+                               gather_field(f, y, x, bb.zero_wire());
+                               bb.unit(f, K + (size_t)o * taps, T + o, 0, oo, flags);
+                           });
+    }
     std::vector<Sig> field(taps);
     // "+1" trick: the popcount of a pixel's receptive field is shared by its output channels
     std::vector<Number> field_sum((flags & TFHE_LOWER_PLUS_ONE) ? (size_t)Ho * Wo : 0);
     for (int o = 0; o < O; ++o)
         for (int y = 0; y < Ho; ++y)
             for (int x = 0; x < Wo; ++x) {
-                size_t t = 0;
-                for (int c = 0; c < C; ++c)
-                    for (int ky = 0; ky < kh; ++ky)
-                        for (int kx = 0; kx < kw; ++kx, ++t) {
-                            const int iy = y * stride + ky - pad, ix = x * stride + kx - pad;
-                            const bool inside = iy >= 0 && iy < H && ix >= 0 && ix < Wd;
-                            field[t] = Sig::of(inside ? (c * H + iy) * Wd + ix : b.zero_wire());
-                        }
+                gather_field(field, y, x, b.zero_wire());
                 const int8_t *w = K + (size_t)o * taps;
                 const bool dense_row = std::all_of(w, w + taps, [](int8_t v) { return v != 0; });
                 if ((flags & TFHE_LOWER_PLUS_ONE) && taps > 1 && dense_row) {
