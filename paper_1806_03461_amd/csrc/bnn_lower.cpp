@@ -363,6 +363,10 @@ int lower_units(int count, size_t work_per_unit, int32_t n_inputs, Builder &b, s
     int threads = (int)std::min<size_t>(std::min<unsigned>(16u, std::max(1u, std::thread::hardware_concurrency())),
                                         (size_t)count);
     if ((size_t)count * work_per_unit < 200000) threads = 1;
+    if (const char *e = getenv("TFHE_LOWER_THREADS")) {           // measurement and tests
+        const int v = atoi(e);
+        if (v >= 1) threads = std::min(v, count);
+    }
     if (threads <= 1) {
         for (int j = 0; j < count; ++j) per_unit(b, outs, j);
         return TFHE_OK;

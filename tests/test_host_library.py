@@ -237,6 +237,25 @@ def test_paper_shaped_networks_lower_to_the_oracle_circuits():
         canonical(cir.gate_array(), oracle_outs(o), cir.n_wires, 288)
 
 
+def test_threaded_lowering_gives_the_serial_records(monkeypatch):
+    """Units lowered by several host threads and appended in order are the very records, wire
+    numbers included, of the one-thread loop (dense and convolution, MUX comparator included)."""
+    rng = np.random.default_rng(5)
+    W = rng.choice(np.array([-1, 0, 1], np.int8), (37, 90), p=[0.45, 0.1, 0.45])
+    Tt = rng.integers(20, 60, 37).astype(np.int32)
+    c4 = workloads.cfg4(C=3, H=6, Wd=7, O=4)
+    results = []
+    for threads in ("1", "5"):
+        monkeypatch.setenv("TFHE_LOWER_THREADS", threads)
+        g1, o1, n1 = T.bnn_dense_lower_opts(90, W, Tt, 37, 0, T.LOWER_MUX_COMPARATOR)
+        g2, o2, n2 = T.bnn_dense_lower(90, W, None, 37, 8)
+        g3, o3, n3 = T.bnn_conv_lower(3, 6, 7, c4["K"], c4["T"] // 6, 1, 1)
+        results.append((g1, o1, n1, g2, o2, n2, g3, o3, n3))
+    for a, b in zip(*results):
+        assert np.array_equal(a, b)
+    assert (results[0][0]["op"] == T.MUX).any() and len(results[0][6]) > 4 * 6 * 7 * 20
+
+
 def test_benchmark_layer_lowering_counts():
     c3 = workloads.cfg3()
     gates, outs, nw = T.bnn_dense_lower(784, c3["W"], c3["T"], 512)
