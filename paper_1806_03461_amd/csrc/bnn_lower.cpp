@@ -356,11 +356,13 @@ int check_weights(const int8_t *W, size_t count) {
 
 // Units that share nothing are lowered by several host threads, each into a builder of its own
 // over a contiguous range of units; appending the parts in order gives exactly the records and
-// wire numbers of the serial loop.  per_unit(builder, outs, j) lowers unit j.
+// wire numbers of the serial loop.  per_unit(builder, outs, j) lowers unit j.  Four threads: the
+// work is allocation-bound and does not scale further (cfg 3 layer: 234 ms on one thread, 104 ms
+// on four, 158 ms on eight).
 template <class PerUnit>
 int lower_units(int count, size_t work_per_unit, int32_t n_inputs, Builder &b, std::vector<tfhe_out_ref> &outs,
                 PerUnit per_unit) {
-    int threads = (int)std::min<size_t>(std::min<unsigned>(16u, std::max(1u, std::thread::hardware_concurrency())),
+    int threads = (int)std::min<size_t>(std::min<unsigned>(4u, std::max(1u, std::thread::hardware_concurrency())),
                                         (size_t)count);
     if ((size_t)count * work_per_unit < 200000) threads = 1;
     if (const char *e = getenv("TFHE_LOWER_THREADS")) {           // measurement and tests
