@@ -131,6 +131,14 @@ enum { TFHE_KEY_LWE_SK = 0,   /* uint32[n], from a secret key */
 /* With buf == NULL stores the byte length in *len; otherwise copies at most *len bytes
  * to buf (HOST) and fails with TFHE_E_SIZE if *len is too small. */
 int tfhe_export_key(const void *key, int which, void *buf, size_t *len);
+/* The inverse of tfhe_export_key: build key objects from raw material in the layouts above
+ * (HOST arrays, copied).  This is how a server receives the cloud key that a client generated
+ * (Sec. 2: the client sends its public evaluation key with the encrypted input).
+ * sk is built when sk != NULL and needs lwe_sk (n words, each 0 or 1) and trlwe_sk (N words);
+ * ck is built when ck != NULL and needs bk_raw and ksk_raw.  Lengths are implied by *p. */
+int tfhe_import_keys(const tfhe_params *p, const uint32_t *lwe_sk, const uint32_t *trlwe_sk,
+                     const uint32_t *bk_raw, const uint32_t *ksk_raw, tfhe_secret_key **sk,
+                     tfhe_cloud_key **ck);
 int tfhe_get_params(const void *key, int is_cloud_key, tfhe_params *out);
 
 void tfhe_free_secret_key(tfhe_secret_key *sk);

@@ -42,7 +42,7 @@ class Profile(C.Structure):
 
 
 EXPORTS = ["tfhe_last_error", "tfhe_default_params", "tfhe_keygen", "tfhe_encrypt", "tfhe_decrypt",
-           "tfhe_trivial", "tfhe_export_key", "tfhe_get_params", "tfhe_free_secret_key",
+           "tfhe_trivial", "tfhe_export_key", "tfhe_import_keys", "tfhe_get_params", "tfhe_free_secret_key",
            "tfhe_free_cloud_key", "tfhe_free_buffer", "tfhe_cloud_key_upload", "tfhe_gate_batch",
            "tfhe_mux_batch", "tfhe_gate_stream", "bnn_dense_lower", "bnn_dense_lower_opts", "bnn_conv_lower",
            "bnn_conv_lower_opts", "bnn_dense_encrypted", "bnn_dense_encrypted_opts", "bnn_conv_encrypted_opts",
@@ -68,6 +68,7 @@ def lib():
         L.tfhe_decrypt.argtypes = [vp, vp, sz, vp]
         L.tfhe_trivial.argtypes = [C.POINTER(Params), i32, vp]
         L.tfhe_export_key.argtypes = [vp, i32, vp, C.POINTER(sz)]
+        L.tfhe_import_keys.argtypes = [C.POINTER(Params), vp, vp, vp, vp, C.POINTER(vp), C.POINTER(vp)]
         L.tfhe_get_params.argtypes = [vp, i32, C.POINTER(Params)]
         L.tfhe_free_secret_key.argtypes = [vp]
         L.tfhe_free_secret_key.restype = None
@@ -189,6 +190,24 @@ def tfhe_export_key(key, which):
     buf = np.empty(ln.value // 4, np.uint32)
     _check(lib().tfhe_export_key(key.handle, which, buf.ctypes.data, C.byref(ln)))
     return buf
+
+
+def tfhe_import_keys(params, lwe_sk=None, trlwe_sk=None, bk_raw=None, ksk_raw=None):
+    """Key objects from raw material (the arrays tfhe_export_key returns).  Returns (sk, ck);
+    sk is None without the two secret arrays, ck is None without the two cloud-key arrays."""
+    want_sk = lwe_sk is not None and trlwe_sk is not None
+    want_ck = bk_raw is not None and ksk_raw is not None
+    arrs = [None if a is None else _host(a, np.uint32).ravel() for a in (lwe_sk, trlwe_sk, bk_raw, ksk_raw)]
+    sizes = (params.n, params.N, params.n * 2 * params.bk_l * 2 * params.N,
+             params.N * params.ks_t * ((1 << params.ks_basebit) - 1) * (params.n + 1))
+    for a, size in zip(arrs, sizes):
+        if a is not None and a.size != size:
+            raise ValueError(f"key array has {a.size} words, the parameters imply {size}")
+    ptrs = [None if a is None else a.ctypes.data for a in arrs]
+    sk, ck = C.c_void_p(), C.c_void_p()
+    _check(lib().tfhe_import_keys(C.byref(params), ptrs[0], ptrs[1], ptrs[2], ptrs[3],
+                                  C.byref(sk) if want_sk else None, C.byref(ck) if want_ck else None))
+    return (SecretKey(sk.value) if want_sk else None), (CloudKey(ck.value) if want_ck else None)
 
 
 def tfhe_cloud_key_upload(ck):

@@ -270,6 +270,53 @@ int tfhe_export_key(const void *key, int which, void *buf, size_t *len) {
     return tfhe::guarded([&]() -> int { return tfhe_export_key_impl(key, which, buf, len); });
 }
 
+static int tfhe_import_keys_impl(const tfhe_params *p, const uint32_t *lwe_sk, const uint32_t *trlwe_sk,
+                                 const uint32_t *bk_raw, const uint32_t *ksk_raw, tfhe_secret_key **sk_out,
+                                 tfhe_cloud_key **ck_out) {
+    if (int rc = tfhe::check_params_host(p)) return rc;
+    if (!sk_out && !ck_out) return set_error(TFHE_E_NULL, "both output pointers are NULL");
+    if (sk_out && (!lwe_sk || !trlwe_sk)) return set_error(TFHE_E_NULL, "a secret key needs lwe_sk and trlwe_sk");
+    if (ck_out && (!bk_raw || !ksk_raw)) return set_error(TFHE_E_NULL, "a cloud key needs bk_raw and ksk_raw");
+    if (sk_out) {
+        for (int j = 0; j < p->n; ++j)
+            if (lwe_sk[j] > 1) return set_error(TFHE_E_PARAM, "lwe_sk[%d] is not a bit", j);
+        for (int j = 0; j < p->N; ++j)
+            if (trlwe_sk[j] > 1) return set_error(TFHE_E_PARAM, "trlwe_sk[%d] is not a bit", j);
+    }
+    tfhe_secret_key *sk = nullptr;
+    tfhe_cloud_key *ck = nullptr;
+    struct Guard {                       // nothing is handed out unless everything succeeded
+        tfhe_secret_key *&sk;
+        tfhe_cloud_key *&ck;
+        ~Guard() { delete sk; delete ck; }
+    } guard{sk, ck};
+    if (sk_out) {
+        sk = new tfhe_secret_key();
+        sk->magic = TFHE_SK_MAGIC;
+        sk->params = *p;
+        sk->lwe.assign(lwe_sk, lwe_sk + p->n);
+        sk->trlwe.assign(trlwe_sk, trlwe_sk + p->N);
+    }
+    if (ck_out) {
+        ck = new tfhe_cloud_key();
+        ck->magic = TFHE_CK_MAGIC;
+        ck->params = *p;
+        ck->bk_raw.assign(bk_raw, bk_raw + (size_t)p->n * tfhe::bk_row_words(*p));
+        ck->ksk_raw.assign(ksk_raw, ksk_raw + tfhe::ksk_rows(*p) * (size_t)(p->n + 1));
+    }
+    if (sk_out) *sk_out = sk;
+    if (ck_out) *ck_out = ck;
+    sk = nullptr; ck = nullptr;
+    return TFHE_OK;
+}
+
+int tfhe_import_keys(const tfhe_params *p, const uint32_t *lwe_sk, const uint32_t *trlwe_sk,
+                     const uint32_t *bk_raw, const uint32_t *ksk_raw, tfhe_secret_key **sk,
+                     tfhe_cloud_key **ck) {
+    return tfhe::guarded(
+        [&]() -> int { return tfhe_import_keys_impl(p, lwe_sk, trlwe_sk, bk_raw, ksk_raw, sk, ck); });
+}
+
 void tfhe_free_secret_key(tfhe_secret_key *sk) {
     if (sk && sk->magic == TFHE_SK_MAGIC) { sk->magic = 0; delete sk; }
 }

@@ -294,3 +294,16 @@ def test_matrix_core_key_switch(gpu, real_keys):
         cir, o = cc.dense_layer(d, W[j:j + 1], Tt[j:j + 1], comparator="mux")
         ref, _ = cc.eval_encrypted(real_keys, cir, ctx, o, threads=16)
         assert np.array_equal(host[j], ref[0]), j
+
+
+def test_imported_cloud_key_serves_gates(gpu, real_keys):
+    """A server that was handed only raw cloud-key material (here: the oracle's own arrays, no
+    secret key involved) evaluates gates to the oracle's bytes."""
+    T, sk, ck = gpu
+    _, served = T.tfhe_import_keys(T.default_params(), bk_raw=real_keys.bk, ksk_raw=real_keys.ksk)
+    rng = np.random.default_rng(31)
+    a, b = rng.integers(0, 2, 9).astype(np.uint8), rng.integers(0, 2, 9).astype(np.uint8)
+    cta, ctb = real_keys.encrypt(a, 111), real_keys.encrypt(b, 112)
+    got = run_batch(T, served, "NOR", cta, ctb)
+    assert np.array_equal(got, oracle_batch(real_keys, "NOR", cta, ctb))
+    assert list(T.tfhe_decrypt(sk, got)) == [int(not (x or y)) for x, y in zip(a, b)]

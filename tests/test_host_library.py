@@ -50,6 +50,36 @@ def test_keygen_matches_oracle_at_benchmark_parameters(real_keys):
     assert np.array_equal(T.tfhe_export_key(ck, T.KEY_KSK_RAW), real_keys.ksk)
 
 
+def test_import_keys_round_trip(orc, small):
+    """Exported raw material imported again gives keys that export the same bytes, encrypt to the
+    same ciphertexts and decrypt them; a server-side cloud key can be built without any secret."""
+    P = small[0]
+    sk, ck = T.tfhe_keygen(P, 77)
+    parts = [T.tfhe_export_key(sk, T.KEY_LWE_SK), T.tfhe_export_key(sk, T.KEY_TRLWE_SK),
+             T.tfhe_export_key(ck, T.KEY_BK_RAW), T.tfhe_export_key(ck, T.KEY_KSK_RAW)]
+    sk2, ck2 = T.tfhe_import_keys(P, *parts)
+    for a, b in ((sk, sk2), (ck, ck2)):
+        assert T.tfhe_get_params(a).n == T.tfhe_get_params(b).n
+    assert np.array_equal(T.tfhe_export_key(sk2, T.KEY_TRLWE_SK), parts[1])
+    assert np.array_equal(T.tfhe_export_key(ck2, T.KEY_BK_RAW), parts[2])
+    assert np.array_equal(T.tfhe_export_key(ck2, T.KEY_KSK_RAW), parts[3])
+    bits = np.array([1, 0, 0, 1, 1], np.uint8)
+    ct = T.tfhe_encrypt(sk2, 5, bits)
+    assert np.array_equal(ct, T.tfhe_encrypt(sk, 5, bits)) and list(T.tfhe_decrypt(sk2, ct)) == list(bits)
+    none_sk, only_ck = T.tfhe_import_keys(P, bk_raw=parts[2], ksk_raw=parts[3])
+    assert none_sk is None and np.array_equal(T.tfhe_export_key(only_ck, T.KEY_KSK_RAW), parts[3])
+    # the oracle's own key material is accepted as well: same formats on both sides
+    K = orc.Keys(orc.Params(*[getattr(P, f) for f, _ in P._fields_]), 77)
+    sk3, ck3 = T.tfhe_import_keys(P, K.lwe_sk, K.trlwe_sk, K.bk, K.ksk)
+    assert np.array_equal(T.tfhe_export_key(ck3, T.KEY_BK_RAW), parts[2])
+    bad = parts[0].copy()
+    bad[0] = 2
+    with pytest.raises(T.TfheError):
+        T.tfhe_import_keys(P, bad, parts[1], parts[2], parts[3])
+    with pytest.raises(ValueError):
+        T.tfhe_import_keys(P, parts[0][:-1], parts[1], parts[2], parts[3])
+
+
 def test_encrypt_decrypt_match_oracle(real_keys):
     sk, _ = T.tfhe_keygen(T.default_params(), workloads.KEY_SEED)
     bits = np.random.default_rng(1).integers(0, 2, 300).astype(np.uint8)
