@@ -265,6 +265,9 @@ __device__ __forceinline__ void blind_rotate_body(const BlindRotateArgs &a) {
         }
         forward_to_slots(x, ln, my.spec[wv], L);
         __syncthreads();
+        // The short phase between the two barriers starts with the key loads: waves in it go first
+        // (measured: 3 % faster than equal priorities; raising it in other phases loses).
+        __builtin_amdgcn_s_setprio(2);
 
         // ---- products with the key row: thread <-> slot, all gates of the workgroup ----
         {
@@ -313,6 +316,7 @@ __device__ __forceinline__ void blind_rotate_body(const BlindRotateArgs &a) {
             }
         }
         __syncthreads();
+        __builtin_amdgcn_s_setprio(0);
         if (AHEAD) load_ahead(i + 1 < a.n ? i + 1 : i);
 
         // ---- inverse transform, exact rounding, accumulate ----
