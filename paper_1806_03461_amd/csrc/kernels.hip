@@ -234,9 +234,10 @@ __device__ __forceinline__ void blind_rotate_body(const BlindRotateArgs &a) {
     };
     if (AHEAD) load_ahead(0);
 
+    int abar_next = my.bar[0];
     for (int i = 0; i < a.n; ++i) {
         // ---- rotate, subtract, decompose, fold and twist ----
-        const int abar = my.bar[i];
+        const int abar = abar_next;          // read one step ahead: off the critical path
         const unsigned char *acc0 = reinterpret_cast<const unsigned char *>(my.acc[0]);
         const uint32_t base = (uint32_t)(L - abar) << 2;       // byte offset of X^abar's source, mod 8192
         // all sixteen rotated reads are issued before any of them is consumed
@@ -318,6 +319,7 @@ __device__ __forceinline__ void blind_rotate_body(const BlindRotateArgs &a) {
         __syncthreads();
         __builtin_amdgcn_s_setprio(0);
         if (AHEAD) load_ahead(i + 1 < a.n ? i + 1 : i);
+        abar_next = my.bar[i + 1];           // bar[n] exists (it holds bbar)
 
         // ---- inverse transform, exact rounding, accumulate ----
         inverse_from_slots(x, ln, my.spec[wv], L);
