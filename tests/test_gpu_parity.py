@@ -3,6 +3,8 @@ oracle, on the same seeded keys and inputs.  All arithmetic is exact modulo 2^32
 bit-for-bit equality; decrypted bits are also checked against plain truth tables / integer layers.
 """
 import itertools
+import os
+import sys
 
 import numpy as np
 import pytest
@@ -307,3 +309,53 @@ def test_imported_cloud_key_serves_gates(gpu, real_keys):
     got = run_batch(T, served, "NOR", cta, ctb)
     assert np.array_equal(got, oracle_batch(real_keys, "NOR", cta, ctb))
     assert list(T.tfhe_decrypt(sk, got)) == [int(not (x or y)) for x, y in zip(a, b)]
+
+
+_CHUNK_SCRIPT = r"""
+import hashlib, sys
+import numpy as np, torch
+sys.path.insert(0, sys.argv[1])
+import paper_1806_03461_amd as T, workloads
+sk, ck = T.tfhe_keygen(T.default_params(), workloads.KEY_SEED)
+rng = np.random.default_rng(95)
+d, p = 11, 5
+W = rng.choice(np.array([-1, 0, 1], np.int8), (p, d), p=[0.45, 0.1, 0.45])
+Tt = np.array([3, 6, 5, 4, 2], np.int32)
+x = rng.integers(0, 2, d).astype(np.uint8)
+ctx = T.to_device(T.tfhe_encrypt(sk, 96, x))
+h = hashlib.sha256()
+for flags in (T.LOWER_MUX_COMPARATOR, T.LOWER_DEFAULT):
+    res = torch.empty((p, 501), dtype=torch.int32, device="cuda")
+    T.bnn_dense_encrypted_opts(ck, ctx, d, W, Tt, p, res, 0, flags)
+    torch.cuda.synchronize()
+    h.update(T.to_host(res).tobytes())
+s = rng.integers(0, 2, 13).astype(np.uint8)
+cs, ca, cb = (T.to_device(T.tfhe_encrypt(sk, 97 + k, s ^ k)) for k in range(3))
+out = torch.empty((13, 501), dtype=torch.int32, device="cuda")
+T.tfhe_mux_batch(ck, cs, ca, cb, out, 13)
+torch.cuda.synchronize()
+h.update(T.to_host(out).tobytes())
+T.tfhe_gate_batch(ck, "XNOR", ca, cb, out, 13)
+torch.cuda.synchronize()
+h.update(T.to_host(out).tobytes())
+print("digest", h.hexdigest())
+"""
+
+
+def test_launch_chunking_does_not_change_results(gpu):
+    """The same calls in a process that splits every launch into chunks of 6 items (levels wider than
+    a chunk, multiplexer pairs at chunk boundaries, many launches per batch) give the same bytes
+    as with the default chunk size."""
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    digests = []
+    for chunk in (None, "6"):
+        env = dict(os.environ)
+        env.pop("TFHE_CHUNK_GATES", None)
+        if chunk:
+            env["TFHE_CHUNK_GATES"] = chunk
+        r = subprocess.run([sys.executable, "-c", _CHUNK_SCRIPT, root], env=env, stdout=subprocess.PIPE,
+                           stderr=subprocess.STDOUT, text=True, timeout=300)
+        assert r.returncode == 0, r.stdout
+        digests.append([l for l in r.stdout.splitlines() if l.startswith("digest")][-1])
+    assert digests[0] == digests[1]
