@@ -104,14 +104,15 @@ int key_switch_group(size_t count) {
     return 1;
 }
 
-// Batches from which the key switch runs as an int8 contraction on the matrix cores.  That
-// kernel takes 0.5-0.7 ms for anything up to 8,192 gates (1,024 dependent steps per workgroup);
-// the gather kernels are faster below about 400 gates.
+// Batches from which the key switch runs as an int8 contraction on the matrix cores: all of them
+// (small batches split each gate's mask words over several workgroups; 16 gates take 0.035 ms
+// against 0.086 ms of the gather kernels, 256 gates 0.065 against 0.42 ms).  The gather kernels
+// remain for parameter sets the matrix kernel does not cover.
 int key_switch_matrix(size_t count) {
     static long threshold = -1;
     if (threshold < 0) {
         const char *e = getenv("TFHE_KS_MATRIX_FROM");
-        threshold = e ? atol(e) : 512;
+        threshold = e ? atol(e) : 1;
     }
     return threshold > 0 && count >= (size_t)threshold;
 }

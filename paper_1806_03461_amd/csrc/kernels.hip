@@ -580,6 +580,7 @@ __global__ __launch_bounds__(256) void ksk_to_tiles_kernel(const uint32_t *__res
     tiles[(((size_t)cb * kN + i) * 4 + plane) * 64 + lane] = t;
 }
 
+template <bool SPLIT>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void key_switch_mfma_kernel(KeySwitchArgs a) {
     extern __shared__ __align__(16) unsigned char lds_raw[];
     KsMatrixLds &lds = *reinterpret_cast<KsMatrixLds *>(lds_raw);
@@ -612,22 +613,33 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     const int byte_shift = 24 - 8 * (lane >> 5);               // digits 0..3 or 4..7 of the word
     const int my_row = wr * 128 + (lane & 31);
 
+    // a.splits workgroups (blockIdx.z) share the 1,024 mask words of their gates: each takes a
+    // contiguous range and adds its partial sum into the zeroed outputs (integer adds commute:
+    // still exact).  That is what gives a small batch enough workgroups to use the whole chip.
+    // (SPLIT = false: one workgroup takes them all, and every loop bound is a constant)
+    const int per_split = SPLIT ? kN / a.splits : kN;           // >= 32, a multiple of kKsAhead
+    const int w_begin = SPLIT ? (int)blockIdx.z * per_split : 0, w_end = w_begin + per_split;
+    const int chunk = SPLIT && per_split < kKsChunk ? per_split : kKsChunk;   // a power of two
+    const int chunk_shift = 31 - __builtin_clz(chunk);
+    const bool wave_live = g0 + (size_t)wr * 128 < a.count;     // none of the wave's 128 gates exists otherwise
+
     // key tiles of the next kKsAhead mask words, in a ring of registers
     v4i ring[kKsAhead][4];
 #pragma unroll
     for (int s = 0; s < kKsAhead; ++s)
 #pragma unroll
-        for (int b = 0; b < 4; ++b) ring[s][b] = tiles[((size_t)s * 4 + b) * 64];
+        for (int b = 0; b < 4; ++b) ring[s][b] = tiles[((size_t)(w_begin + s) * 4 + b) * 64];
 
-    for (int i0 = 0; i0 < kN; i0 += kKsChunk) {
+    for (int i0 = w_begin; i0 < w_end; i0 += chunk) {
         __syncthreads();                                        // the previous chunk has been consumed
-        // 32 lanes read 32 consecutive mask words of one gate; a dead gate stages all-zero digits
-        for (int idx = tid; idx < kKsChunk * kKsRows; idx += 256) {
-            const int g = idx / kKsChunk, ii = idx % kKsChunk;
+        // consecutive lanes read consecutive mask words of one gate; a dead gate stages all-zero digits
+        for (int idx = tid; idx < chunk * kKsRows; idx += 256) {
+            const int g = idx >> chunk_shift, ii = idx & (chunk - 1);
             mask_words[ii][g] = out_row[g] >= 0 ? a.ext[(g0 + g) * (size_t)(kN + 1) + i0 + ii] + round : 0u;
         }
         __syncthreads();
-        for (int i1 = 0; i1 < kKsChunk; i1 += kKsAhead) {
+        if (!wave_live) continue;
+        for (int i1 = 0; i1 < chunk; i1 += kKsAhead) {
 #pragma unroll
             for (int s = 0; s < kKsAhead; ++s) {
                 const int ii = i1 + s;
@@ -662,8 +674,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
                 if (row < 0) continue;
                 const uint32_t sum = (uint32_t)acc[rt][0][r] + ((uint32_t)acc[rt][1][r] << 8) +
                                      ((uint32_t)acc[rt][2][r] << 16) + ((uint32_t)acc[rt][3][r] << 24);
-                const uint32_t body = c == a.n ? a.ext[(g0 + g) * (size_t)(kN + 1) + kN] : 0u;
-                a.out[(size_t)row * words + c] = body - sum;
+                const uint32_t body = (c == a.n && (!SPLIT || blockIdx.z == 0)) ? a.ext[(g0 + g) * (size_t)(kN + 1) + kN] : 0u;
+                if (SPLIT) atomicAdd(a.out + (size_t)row * words + c, body - sum);
+                else a.out[(size_t)row * words + c] = body - sum;
             }
     }
 }
@@ -792,12 +805,26 @@ int launch_key_switch(const KeySwitchArgs &a, hipStream_t stream) {
     if (a.ksk_tiles && a.matrix && a.t == 8 && a.basebit == 2 && a.n + 1 <= 512) {
         static bool configured = false;
         if (!configured) {
-            TFHE_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&key_switch_mfma_kernel),
+            TFHE_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&key_switch_mfma_kernel<false>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(KsMatrixLds)));
+            TFHE_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&key_switch_mfma_kernel<true>),
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(KsMatrixLds)));
             configured = true;
         }
-        const dim3 grid((unsigned)((a.count + kKsRows - 1) / kKsRows), 8);
-        hipLaunchKernelGGL(key_switch_mfma_kernel, grid, dim3(256), sizeof(KsMatrixLds), stream, a);
+        // fewer than one workgroup per CU: share each gate's mask words between workgroups
+        KeySwitchArgs m = a;
+        const unsigned row_blocks = (unsigned)((a.count + kKsRows - 1) / kKsRows);
+        m.splits = 1;
+        while (m.splits < 32 && row_blocks * 8 * m.splits < 256) m.splits *= 2;
+        if (m.splits > 1) {
+            hipLaunchKernelGGL(zero_outputs_kernel, dim3((unsigned)a.count), dim3(256), 0, stream, m);
+            TFHE_HIP(hipGetLastError());
+        }
+        const dim3 grid(row_blocks, 8, (unsigned)m.splits);
+        if (m.splits > 1)
+            hipLaunchKernelGGL(key_switch_mfma_kernel<true>, grid, dim3(256), sizeof(KsMatrixLds), stream, m);
+        else
+            hipLaunchKernelGGL(key_switch_mfma_kernel<false>, grid, dim3(256), sizeof(KsMatrixLds), stream, m);
         TFHE_HIP(hipGetLastError());
         return TFHE_OK;
     }

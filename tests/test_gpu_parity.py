@@ -255,7 +255,7 @@ def test_mux_gate_batch_and_stream(gpu, real_keys):
 
 
 def test_matrix_core_key_switch(gpu, real_keys):
-    """Batches of 512 launch items and more switch keys with the int8 matrix-core kernel: a ragged
+    """The int8 matrix-core key switch on batches wide enough for whole workgroups: a ragged
     batch (two full 256-gate workgroups and a tail) whole against the oracle, a multiplexer batch
     (every second launch item writes nothing), and a gate stream whose records carry scattered
     output wires and multiplexer pairs."""
