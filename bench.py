@@ -67,7 +67,7 @@ def main():
     ap.add_argument("--share", action="store_true",
                     help="emit identical gates of different units once (structural sharing)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
-    ap.add_argument("--cpu-gates", type=int, default=512, help="gates in the oracle sample")
+    ap.add_argument("--cpu-gates", type=int, default=2048, help="gates in the oracle sample")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
                     help="after the timed steps, run one plain device-to-device copy of this size "
                          "(a known-traffic kernel to scale rocprofv3's FETCH_SIZE / WRITE_SIZE by)")
@@ -250,18 +250,20 @@ def main():
         threads = min(16, os.cpu_count() or 1)
         ng = args.cpu_gates
         if c is not None or net is not None:
-            # the first ng gates of the (first) layer's circuit are first-level gates: inputs only
+            # gates of the (first) layer's circuit that read only inputs: the first ng of them, their
+            # outputs renumbered to a compact wire array
             if net is not None:
                 d = d_first
-                inner = np.maximum(gates_host["in0"], gates_host["in1"]) >= d + 2
-                ng = min(ng, int(inner.argmax()) if inner.any() else len(inner))
-            sample = np.array(gates_host[:ng], dtype=orc.GATE_DTYPE)
             nin = d + 2
-            wires = np.zeros((int(sample["out"].max()) + 1, words), np.uint32)
+            first_level = np.flatnonzero((np.maximum(gates_host["in0"], gates_host["in1"]) < nin) &
+                                         (gates_host["op"] < T.MUX))[:ng]
+            ng = len(first_level)
+            sample = np.array(gates_host[first_level], dtype=orc.GATE_DTYPE)
+            sample["out"] = nin + np.arange(ng)
+            wires = np.zeros((nin + ng, words), np.uint32)
             wires[:d] = T.to_host(x)
             wires[d], wires[d + 1] = keys.trivial(0), keys.trivial(1)
-            assert int(max(sample["in0"].max(), sample["in1"].max())) < nin
-            what = f"first {ng} gates of the {args.workload} gate stream"
+            what = f"{ng} first-level gates of the {args.workload} gate stream"
         else:
             ng = min(ng, cnt)
             sample = np.array([(0, 0, 0, 0, i, ng + i, 2 * ng + i) for i in range(ng)], dtype=orc.GATE_DTYPE)
