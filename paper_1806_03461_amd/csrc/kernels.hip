@@ -14,6 +14,7 @@
 // makes this cheaper than any 32-bit-integer number-theoretic transform on its VALU.
 #include <hip/hip_runtime.h>
 
+#include <cstddef>
 #include <cstdlib>
 
 #include "common.h"
@@ -118,6 +119,8 @@ struct GateLds {
     uint32_t acc[2][kN];          // accumulator: mask, body
     uint16_t bar[1032];           // abar_0 .. abar_{n-1}, bbar
 };
+// the rotation or-s a masked offset into the accumulator's address (dynamic LDS starts at 0)
+static_assert(offsetof(GateLds, acc) % (kN * sizeof(uint32_t)) == 0, "accumulator must be 4 KB aligned");
 
 __device__ __forceinline__ void gate_constants(int op, uint32_t &kappa, uint32_t &mult) {
     switch (op) {
@@ -128,6 +131,13 @@ __device__ __forceinline__ void gate_constants(int op, uint32_t &kappa, uint32_t
     case TFHE_XOR:  kappa = 2u * kEighth;     mult = 2u;          break;
     default:        kappa = 0u - 2u * kEighth; mult = 0xFFFFFFFEu; break;   // XNOR
     }
+}
+
+// (x & mask) | y in one instruction; mask is wave-uniform
+__device__ __forceinline__ uint32_t and_or(uint32_t x, uint32_t mask, uint32_t y) {
+    uint32_t r;
+    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(x), "s"(mask), "v"(y));
+    return r;
 }
 
 // 16-byte load from a buffer: descriptor and soffset are scalar, voffset is the lane's byte offset
@@ -213,8 +223,7 @@ __device__ __forceinline__ void blind_rotate_body(const BlindRotateArgs &a) {
     // field to the top of the word, shift back down arithmetically.
     const uint32_t dround = 1u << (31 - 2 * a.bgbit);
     const uint32_t doffset = sel ? dround : dround + (1u << (31 - a.bgbit));
-    const int dlsh = sel ? a.bgbit : 0;
-    const int drsh = 32 - a.bgbit;
+    const uint32_t dfield = (uint32_t)(32 - a.bgbit * (1 + sel));   // lowest bit of the digit's field
     double worst = 0.0;
 
     constexpr int kSlotsPerThread = (kHalf + kThreadsPerGate * B - 1) / (kThreadsPerGate * B);
@@ -237,17 +246,33 @@ __device__ __forceinline__ void blind_rotate_body(const BlindRotateArgs &a) {
     int abar_next = my.bar[0];
     for (int i = 0; i < a.n; ++i) {
         // ---- rotate, subtract, decompose, fold and twist ----
-        const int abar = abar_next;          // read one step ahead: off the critical path
-        const unsigned char *acc0 = reinterpret_cast<const unsigned char *>(my.acc[0]);
-        const uint32_t base = (uint32_t)(L - abar) << 2;       // byte offset of X^abar's source, mod 8192
+        // read one step ahead (off the critical path); the same in every lane, so it goes to a scalar
+        // register and the per-coefficient offsets below are scalar arithmetic
+        const int abar = __builtin_amdgcn_readfirstlane(abar_next);
+        // LDS address of the component's accumulator as an integer: 4 KB aligned when the workgroup holds
+        // one gate, so that a masked offset is or-ed in
+        typedef __attribute__((address_space(3))) const uint32_t lds_word;
+        const uint32_t acc_at = (uint32_t)(uintptr_t)(lds_word *)my.acc[comp];
+        const uint32_t lane4 = (uint32_t)L << 2;
+        const uint32_t back4 = (uint32_t)(0 - abar) << 2;       // X^abar reads abar coefficients back, mod 8192 bytes
+        // per coefficient: byte offset of its source = lane part + scalar part (kept on the scalar ALU)
+        uint32_t shift4[8][2];
+#pragma unroll
+        for (int m = 0; m < 8; ++m)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                shift4[m][h] = back4 + (uint32_t)(64 * m + h * kHalf) * 4u;
+                asm("" : "+s"(shift4[m][h]));
+            }
         // all sixteen rotated reads are issued before any of them is consumed
         uint32_t rot[8][2];
 #pragma unroll
         for (int m = 0; m < 8; ++m)
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
-                const uint32_t src = base + (uint32_t)(64 * m + h * kHalf) * 4u;
-                rot[m][h] = *reinterpret_cast<const uint32_t *>(acc0 + ((src & 4092u) | ((uint32_t)comp << 12)));
+                const uint32_t src = lane4 + shift4[m][h];
+                const uint32_t at = B == 1 ? and_or(src, 4092u, acc_at) : (src & 4092u) + acc_at;
+                rot[m][h] = *(lds_word *)(uintptr_t)at;
             }
         double2 x[8];
 #pragma unroll
@@ -256,11 +281,11 @@ __device__ __forceinline__ void blind_rotate_body(const BlindRotateArgs &a) {
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
                 const int j = L + 64 * m + h * kHalf;
-                const uint32_t src = base + (uint32_t)(64 * m + h * kHalf) * 4u;
+                const uint32_t src = lane4 + shift4[m][h];
                 const uint32_t past = (src >> 12) & 1u;                         // source lies past X^N: negate
                 // +-p - acc[j] + doffset, with -p = (p ^ ~0) + 1
                 const uint32_t d = (rot[m][h] ^ (0u - past)) + (doffset - my.acc[comp][j]) + past;
-                dig[h] = (int32_t)(d << dlsh) >> drsh;
+                dig[h] = __builtin_amdgcn_sbfe((int32_t)d, dfield, (uint32_t)a.bgbit);    // signed field
             }
             x[m] = make_double2((double)dig[0], (double)dig[1]);
         }
