@@ -116,7 +116,7 @@ __global__ __launch_bounds__(64) void bk_to_spectrum_kernel(const uint32_t *__re
 // ------------------------------------------------------------------------------------------
 struct GateLds {
     double2 spec[4][kBufWords];   // per wave: FFT scratch, then spectrum / product in slot order
-    uint32_t acc[2][kN];          // accumulator: mask, body
+    uint32_t acc[2][kN];          // accumulator (mask, body), stored bitwise complemented: ~ACC = -ACC - 1
     uint16_t bar[1032];           // abar_0 .. abar_{n-1}, bbar
 };
 // the rotation or-s a masked offset into the accumulator's address (dynamic LDS starts at 0)
@@ -210,8 +210,8 @@ __device__ __forceinline__ void blind_rotate_body(const BlindRotateArgs &a) {
         const int bb = bbar & (kN - 1);
         const uint32_t first = bbar < kN ? kEighth : 0u - kEighth;   // X^-bbar v, closed form
         for (int j = lt; j < kN; j += kThreadsPerGate) {
-            my.acc[0][j] = 0;
-            my.acc[1][j] = j < kN - bb ? first : 0u - first;
+            my.acc[0][j] = ~0u;
+            my.acc[1][j] = ~(j < kN - bb ? first : 0u - first);
         }
     }
     __syncthreads();
@@ -261,7 +261,8 @@ __device__ __forceinline__ void blind_rotate_body(const BlindRotateArgs &a) {
         for (int m = 0; m < 8; ++m)
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
-                shift4[m][h] = back4 + (uint32_t)(64 * m + h * kHalf) * 4u;
+                // + 4096: bit 12 of the sum then says "source not past X^N"
+                shift4[m][h] = back4 + (uint32_t)(64 * m + h * kHalf) * 4u + 4096u;
                 asm("" : "+s"(shift4[m][h]));
             }
         // all sixteen rotated reads are issued before any of them is consumed
@@ -282,9 +283,12 @@ __device__ __forceinline__ void blind_rotate_body(const BlindRotateArgs &a) {
             for (int h = 0; h < 2; ++h) {
                 const int j = L + 64 * m + h * kHalf;
                 const uint32_t src = lane4 + shift4[m][h];
-                const uint32_t past = (src >> 12) & 1u;                         // source lies past X^N: negate
-                // +-p - acc[j] + doffset, with -p = (p ^ ~0) + 1
-                const uint32_t d = (rot[m][h] ^ (0u - past)) + (doffset - my.acc[comp][j]) + past;
+                // With ACC stored as c = ~ACC, the step's  +-ACC[src] - ACC[j] + doffset  is
+                //   source not past X^N:  -c[src] + c[j] + doffset = (c[src] ^ ~0) + c[j] + doffset + 1
+                //   source past X^N:       c[src] + c[j] + doffset + 2
+                // i.e. (c[src] ^ flip) + c[j] + (doffset + 2 + flip) with flip = ~0 or 0: four instructions.
+                const uint32_t flip = (uint32_t)__builtin_amdgcn_sbfe((int32_t)src, 12u, 1u);
+                const uint32_t d = (rot[m][h] ^ flip) + my.acc[comp][j] + (doffset + 2u + flip);
                 dig[h] = __builtin_amdgcn_sbfe((int32_t)d, dfield, (uint32_t)a.bgbit);    // signed field
             }
             x[m] = make_double2((double)dig[0], (double)dig[1]);
@@ -353,10 +357,11 @@ __device__ __forceinline__ void blind_rotate_body(const BlindRotateArgs &a) {
             const double part[2] = {x[m].x, x[m].y};
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
-                // adding 1.5 * 2^52 leaves round-to-nearest(part) mod 2^32 in the low word
-                const double shifted = part[h] + 6755399441055744.0;
+                // 1.5 * 2^52 - part leaves round-to-nearest(-part) = -round(part) mod 2^32 in the low word
+                // (ties go to even either way); the complemented accumulator takes it: ~(ACC + r) = ~ACC - r
+                const double shifted = 6755399441055744.0 - part[h];
                 uint32_t r = (uint32_t)__double2loint(shifted);
-                if (MARGIN) worst = fmax(worst, fabs(part[h] - (shifted - 6755399441055744.0)));
+                if (MARGIN) worst = fmax(worst, fabs(part[h] + (shifted - 6755399441055744.0)));
                 if (sel) r <<= 16;
                 atomicAdd(&my.acc[comp][L + 64 * m + h * kHalf], r);
             }
@@ -367,8 +372,9 @@ __device__ __forceinline__ void blind_rotate_body(const BlindRotateArgs &a) {
     // ---- epilogue: the constant coefficient as an LWE sample under the ring key ----
     if (live) {
         uint32_t *ext = a.ext + gi * (size_t)(kN + 1);
-        for (int j = lt; j < kN; j += kThreadsPerGate) ext[j] = j == 0 ? my.acc[0][0] : 0u - my.acc[0][kN - j];
-        if (lt == 0) ext[kN] = my.acc[1][0];
+        // ACC = ~c, -ACC = c + 1
+        for (int j = lt; j < kN; j += kThreadsPerGate) ext[j] = j == 0 ? ~my.acc[0][0] : my.acc[0][kN - j] + 1u;
+        if (lt == 0) ext[kN] = ~my.acc[1][0];
     }
     if (MARGIN) {
         // non-negative doubles order like their bit patterns
