@@ -119,8 +119,8 @@ struct GateLds {
     uint32_t acc[2][kN];          // accumulator (mask, body), stored bitwise complemented: ~ACC = -ACC - 1
     uint16_t bar[1032];           // abar_0 .. abar_{n-1}, bbar
 };
-// the rotation or-s a masked offset into the accumulator's address (dynamic LDS starts at 0)
-static_assert(offsetof(GateLds, acc) % (kN * sizeof(uint32_t)) == 0, "accumulator must be 4 KB aligned");
+// the rotation or-s a masked offset into the accumulator's address when that is 4 KB aligned
+static_assert(offsetof(GateLds, acc) % (kN * sizeof(uint32_t)) == 0, "accumulator at a multiple of 4 KB");
 
 __device__ __forceinline__ void gate_constants(int op, uint32_t &kappa, uint32_t &mult) {
     switch (op) {
@@ -250,7 +250,7 @@ __device__ __forceinline__ void blind_rotate_body(const BlindRotateArgs &a) {
         // register and the per-coefficient offsets below are scalar arithmetic
         const int abar = __builtin_amdgcn_readfirstlane(abar_next);
         // LDS address of the component's accumulator as an integer: 4 KB aligned when the workgroup holds
-        // one gate, so that a masked offset is or-ed in
+        // one gate (dynamic LDS starts at 0), so that a masked offset can be or-ed in
         typedef __attribute__((address_space(3))) const uint32_t lds_word;
         const uint32_t acc_at = (uint32_t)(uintptr_t)(lds_word *)my.acc[comp];
         const uint32_t lane4 = (uint32_t)L << 2;
@@ -267,14 +267,19 @@ __device__ __forceinline__ void blind_rotate_body(const BlindRotateArgs &a) {
             }
         // all sixteen rotated reads are issued before any of them is consumed
         uint32_t rot[8][2];
+        if ((acc_at & 4095u) == 0) {              // wave-uniform; true for one gate per workgroup
 #pragma unroll
-        for (int m = 0; m < 8; ++m)
+            for (int m = 0; m < 8; ++m)
 #pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                const uint32_t src = lane4 + shift4[m][h];
-                const uint32_t at = B == 1 ? and_or(src, 4092u, acc_at) : (src & 4092u) + acc_at;
-                rot[m][h] = *(lds_word *)(uintptr_t)at;
-            }
+                for (int h = 0; h < 2; ++h)
+                    rot[m][h] = *(lds_word *)(uintptr_t)and_or(lane4 + shift4[m][h], 4092u, acc_at);
+        } else {
+#pragma unroll
+            for (int m = 0; m < 8; ++m)
+#pragma unroll
+                for (int h = 0; h < 2; ++h)
+                    rot[m][h] = *(lds_word *)(uintptr_t)(((lane4 + shift4[m][h]) & 4092u) + acc_at);
+        }
         double2 x[8];
 #pragma unroll
         for (int m = 0; m < 8; ++m) {
