@@ -70,34 +70,32 @@ namespace {
 // Launch items per kernel pair.  A launch ends with CUs idling until its slowest workgroup is done
 // (about one gate latency), so a circuit level should be one launch where it can; the limit only
 // bounds the extract workspace (4,100 B per item: 1.07 GB).
+// an environment override, read once (function-local statics initialise thread-safely)
+long env_long(const char *name, long fallback) {
+    const char *e = getenv(name);
+    return e ? atol(e) : fallback;
+}
+
 size_t chunk_gates() {
-    static size_t cached = 0;
-    if (!cached) {
-        const char *e = getenv("TFHE_CHUNK_GATES");
-        const long v = e ? atol(e) : 0;
-        cached = v >= 2 ? (size_t)v & ~(size_t)1 : (size_t)1 << 18;
-    }
+    static const size_t cached = [] {
+        const long v = env_long("TFHE_CHUNK_GATES", 0);
+        return v >= 2 ? (size_t)v & ~(size_t)1 : (size_t)1 << 18;
+    }();
     return cached;
 }
 
 int gates_per_group() {
-    static int cached = 0;
-    if (!cached) {
-        const char *e = getenv("TFHE_GATES_PER_GROUP");
-        int v = e ? atoi(e) : 0;
-        cached = (v >= 1 && v <= 3) ? v : 1;
-    }
+    static const int cached = [] {
+        const long v = env_long("TFHE_GATES_PER_GROUP", 1);
+        return (v >= 1 && v <= 3) ? (int)v : 1;
+    }();
     return cached;
 }
 
 // Gates per key-switch workgroup: large batches amortise the 49 MB key over 16 gates; small
 // batches (the deep, narrow levels of a circuit) need many short workgroups instead.
 int key_switch_group(size_t count) {
-    static int forced = -1;
-    if (forced < 0) {
-        const char *e = getenv("TFHE_KS_GROUP");
-        forced = e ? atoi(e) : 0;
-    }
+    static const int forced = (int)env_long("TFHE_KS_GROUP", 0);
     if (forced > 0) return forced;
     if (count >= 8192) return 16;
     if (count >= 2048) return 4;
@@ -109,11 +107,7 @@ int key_switch_group(size_t count) {
 // against 0.086 ms of the gather kernels, 256 gates 0.065 against 0.42 ms).  The gather kernels
 // remain for parameter sets the matrix kernel does not cover.
 int key_switch_matrix(size_t count) {
-    static long threshold = -1;
-    if (threshold < 0) {
-        const char *e = getenv("TFHE_KS_MATRIX_FROM");
-        threshold = e ? atol(e) : 1;
-    }
+    static const long threshold = env_long("TFHE_KS_MATRIX_FROM", 1);
     return threshold > 0 && count >= (size_t)threshold;
 }
 
@@ -159,8 +153,7 @@ int run_batch(tfhe_cloud_key *ck, const tfhe_gate_rec *d_recs, int uniform_op, c
     // workgroups so that the whole chip works on the batch
     ks.splits = 1;
     if (ks.group == 1) {
-        static int forced = -1;
-        if (forced < 0) { const char *e = getenv("TFHE_KS_SPLITS"); forced = e ? atoi(e) : 0; }
+        static const int forced = (int)env_long("TFHE_KS_SPLITS", 0);
         if (forced > 0) ks.splits = forced;
         else while (ks.splits < 16 && count * ks.splits < 4096) ks.splits *= 2;
     }

@@ -14,6 +14,7 @@
 // makes this cheaper than any 32-bit-integer number-theoretic transform on its VALU.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cstddef>
 #include <cstdlib>
 
@@ -754,17 +755,27 @@ __global__ void fill_trivial_kernel(uint32_t *ct, int words, uint32_t body) {
 
 // Largest batch that goes to the latency variant: one gate per compute unit of the device.
 static int latency_batch_limit() {
-    static int limit = -1;
-    if (limit < 0) {
-        const char *e = getenv("TFHE_LATENCY_BATCH");
+    static const int limit = [] {
+        if (const char *e = getenv("TFHE_LATENCY_BATCH")) return atoi(e);
         int dev = 0, cus = 0;
-        if (e) limit = atoi(e);
-        else if (hipGetDevice(&dev) == hipSuccess &&
-                 hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess)
-            limit = cus;
-        else limit = 0;
-    }
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess)
+            return cus;
+        return 0;
+    }();
     return limit;
+}
+
+// Kernels that use more than 64 KB of dynamic LDS have to be told so once per device;
+// `done` is that kernel's own bit mask of devices.
+static int allow_dynamic_lds(const void *kernel, size_t bytes, std::atomic<uint64_t> &done) {
+    int dev = 0;
+    TFHE_HIP(hipGetDevice(&dev));
+    const uint64_t bit = 1ull << (dev & 63);
+    if (done.load(std::memory_order_acquire) & bit) return TFHE_OK;
+    TFHE_HIP(hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes));
+    done.fetch_or(bit, std::memory_order_release);
+    return TFHE_OK;
 }
 
 size_t blind_rotate_lds_bytes(int gates_per_group) { return sizeof(GateLds) * (size_t)gates_per_group; }
@@ -780,14 +791,9 @@ int launch_bk_to_spectrum(const uint32_t *bk_raw, double2 *bk_fft, const double2
 template <int B>
 static int launch_br(const BlindRotateArgs &a, hipStream_t stream) {
     const size_t lds = blind_rotate_lds_bytes(B);
-    static bool configured = false;
-    if (!configured) {
-        TFHE_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&blind_rotate_kernel<B, false>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        TFHE_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&blind_rotate_kernel<B, true>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        configured = true;
-    }
+    static std::atomic<uint64_t> plain{0}, with_margin{0};
+    if (int rc = allow_dynamic_lds(reinterpret_cast<const void *>(&blind_rotate_kernel<B, false>), lds, plain)) return rc;
+    if (int rc = allow_dynamic_lds(reinterpret_cast<const void *>(&blind_rotate_kernel<B, true>), lds, with_margin)) return rc;
     const unsigned blocks = (unsigned)((a.count + B - 1) / B);
     if (a.margin)
         hipLaunchKernelGGL((blind_rotate_kernel<B, true>), dim3(blocks), dim3(kThreadsPerGate * B), lds, stream, a);
@@ -800,14 +806,9 @@ static int launch_br(const BlindRotateArgs &a, hipStream_t stream) {
 // Batches that leave at most one gate per CU: the variant that loads each key row a step ahead.
 static int launch_br_latency(const BlindRotateArgs &a, hipStream_t stream) {
     const size_t lds = blind_rotate_lds_bytes(1);
-    static bool configured = false;
-    if (!configured) {
-        TFHE_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&blind_rotate_latency_kernel<false>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        TFHE_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&blind_rotate_latency_kernel<true>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        configured = true;
-    }
+    static std::atomic<uint64_t> plain{0}, with_margin{0};
+    if (int rc = allow_dynamic_lds(reinterpret_cast<const void *>(&blind_rotate_latency_kernel<false>), lds, plain)) return rc;
+    if (int rc = allow_dynamic_lds(reinterpret_cast<const void *>(&blind_rotate_latency_kernel<true>), lds, with_margin)) return rc;
     if (a.margin)
         hipLaunchKernelGGL(blind_rotate_latency_kernel<true>, dim3((unsigned)a.count), dim3(kThreadsPerGate), lds, stream, a);
     else
@@ -839,14 +840,11 @@ size_t ksk_tiles_bytes() { return (size_t)16 * kN * 4 * 64 * sizeof(v4i); }
 int launch_key_switch(const KeySwitchArgs &a, hipStream_t stream) {
     if (a.count == 0) return TFHE_OK;
     if (a.ksk_tiles && a.matrix && a.t == 8 && a.basebit == 2 && a.n + 1 <= 512) {
-        static bool configured = false;
-        if (!configured) {
-            TFHE_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&key_switch_mfma_kernel<false>),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(KsMatrixLds)));
-            TFHE_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&key_switch_mfma_kernel<true>),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(KsMatrixLds)));
-            configured = true;
-        }
+        static std::atomic<uint64_t> whole{0}, split{0};
+        if (int rc = allow_dynamic_lds(reinterpret_cast<const void *>(&key_switch_mfma_kernel<false>), sizeof(KsMatrixLds), whole))
+            return rc;
+        if (int rc = allow_dynamic_lds(reinterpret_cast<const void *>(&key_switch_mfma_kernel<true>), sizeof(KsMatrixLds), split))
+            return rc;
         // fewer than one workgroup per CU: share each gate's mask words between workgroups
         KeySwitchArgs m = a;
         const unsigned row_blocks = (unsigned)((a.count + kKsRows - 1) / kKsRows);
