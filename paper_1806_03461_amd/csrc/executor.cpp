@@ -126,9 +126,27 @@ int begin_timed(tfhe_cloud_key *ck, int kind, hipStream_t stream, TimedLaunch &t
     return TFHE_OK;
 }
 
+// Add the finished event pairs to the totals and release them.
+int drain_timed(tfhe_cloud_key *ck) {
+    for (auto &tl : ck->timed) {
+        TFHE_HIP(hipEventSynchronize(tl.stop));
+        float ms = 0;
+        TFHE_HIP(hipEventElapsedTime(&ms, tl.start, tl.stop));
+        ck->prof_ms[tl.kind] += ms;
+        ck->prof_launches[tl.kind] += 1;
+        (void)hipEventDestroy(tl.start);
+        (void)hipEventDestroy(tl.stop);
+    }
+    ck->timed.clear();
+    return TFHE_OK;
+}
+
 int end_timed(tfhe_cloud_key *ck, hipStream_t stream, TimedLaunch &tl) {
     TFHE_HIP(hipEventRecord(tl.stop, stream));
     ck->timed.push_back(tl);
+    // a caller that never reads the profile must not pile up events: fold them in now and then
+    // (this waits for the launches so far; profiling is a measurement mode)
+    if (ck->timed.size() >= 4096) return drain_timed(ck);
     return TFHE_OK;
 }
 
@@ -414,16 +432,7 @@ int tfhe_profile_enable(tfhe_cloud_key *ck, int on) {
 static int tfhe_profile_read_impl(tfhe_cloud_key *ck, tfhe_profile *out, int reset) {
     if (int rc = check_cloud_key(ck)) return rc;
     if (!out) return set_error(TFHE_E_NULL, "NULL profile output");
-    for (auto &tl : ck->timed) {
-        TFHE_HIP(hipEventSynchronize(tl.stop));
-        float ms = 0;
-        TFHE_HIP(hipEventElapsedTime(&ms, tl.start, tl.stop));
-        ck->prof_ms[tl.kind] += ms;
-        ck->prof_launches[tl.kind] += 1;
-        (void)hipEventDestroy(tl.start);
-        (void)hipEventDestroy(tl.stop);
-    }
-    ck->timed.clear();
+    if (int rc = drain_timed(ck)) return rc;
     out->blind_rotate_ms = ck->prof_ms[0];
     out->key_switch_ms = ck->prof_ms[1];
     out->blind_rotate_launches = ck->prof_launches[0];
