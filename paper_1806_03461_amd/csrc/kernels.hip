@@ -156,15 +156,20 @@ __device__ __forceinline__ double2 load_key(__amdgpu_buffer_rsrc_t rsrc, uint32_
 // done, so that their latency hides behind the inverse transforms, the rotation and the
 // forward transforms.  All of them only for launches that leave one workgroup per CU; at full
 // occupancy other workgroups already cover that latency (one part ahead: no measurable gain).
-template <int B, bool MARGIN, int AHEAD>
+// TPG: threads per gate, 256 or 512.  The transforms, the rotation and the accumulation are the
+// work of four waves; with 512 threads the other four waves only take their share of the
+// spectral products (one slot per thread instead of two), which shortens a lone gate's step.
+template <int B, bool MARGIN, int AHEAD, int TPG = kThreadsPerGate>
 __device__ __forceinline__ void blind_rotate_body(const BlindRotateArgs &a) {
     extern __shared__ __align__(16) unsigned char lds_raw[];
     GateLds *lds = reinterpret_cast<GateLds *>(lds_raw);
 
     const int tid = threadIdx.x;
-    const int g = tid >> 8;                // gate slot in this workgroup
-    const int lt = tid & 255;              // thread within the gate
+    static_assert(TPG == 256 || TPG == 512, "four or eight waves per gate");
+    const int g = tid / TPG;               // gate slot in this workgroup
+    const int lt = tid % TPG;              // thread within the gate
     const int wv = lt >> 6;                // wave within the gate
+    const bool fft_wave = TPG == 256 || wv < 4;    // wave-uniform
     const int L = tid & 63;
     GateLds &my = lds[g];
     const size_t gi = (size_t)blockIdx.x * B + g;
@@ -196,7 +201,7 @@ __device__ __forceinline__ void blind_rotate_body(const BlindRotateArgs &a) {
         uint32_t kappa, mult;
         gate_constants(op, kappa, mult);
         const size_t w = (size_t)a.n + 1;
-        for (int j = lt; j <= a.n; j += kThreadsPerGate) {
+        for (int j = lt; j <= a.n; j += TPG) {
             uint32_t c = 0;
             if (live) {
                 c = mult * (s0 * a.in0[i0 * w + j] + s1 * src1[i1 * w + j]);
@@ -210,14 +215,14 @@ __device__ __forceinline__ void blind_rotate_body(const BlindRotateArgs &a) {
         const int bbar = my.bar[a.n];
         const int bb = bbar & (kN - 1);
         const uint32_t first = bbar < kN ? kEighth : 0u - kEighth;   // X^-bbar v, closed form
-        for (int j = lt; j < kN; j += kThreadsPerGate) {
+        for (int j = lt; j < kN; j += TPG) {
             my.acc[0][j] = ~0u;
             my.acc[1][j] = ~(j < kN - bb ? first : 0u - first);
         }
     }
     __syncthreads();
 
-    const int comp = wv >> 1;                   // forward: component of D; inverse: component of ACC
+    const int comp = (wv & 3) >> 1;             // forward: component of D; inverse: component of ACC
     const int sel = wv & 1;                     // forward: digit index; inverse: limb
     // Signed digit `sel` of x: add the rounding constant and the half-bases of the lower digits
     // (not its own: its two's-complement field then already is the centred digit), move the
@@ -227,7 +232,7 @@ __device__ __forceinline__ void blind_rotate_body(const BlindRotateArgs &a) {
     const uint32_t dfield = (uint32_t)(32 - a.bgbit * (1 + sel));   // lowest bit of the digit's field
     double worst = 0.0;
 
-    constexpr int kSlotsPerThread = (kHalf + kThreadsPerGate * B - 1) / (kThreadsPerGate * B);
+    constexpr int kSlotsPerThread = (kHalf + TPG * B - 1) / (TPG * B);
     static_assert(AHEAD >= 0 && AHEAD <= 2 * kSlotsPerThread, "parts of one step");
     double2 ahead[AHEAD ? AHEAD : 1][4][2];     // [part = 2 * pass + half][row][output]
     auto load_ahead = [&](int row) {
@@ -239,13 +244,15 @@ __device__ __forceinline__ void blind_rotate_body(const BlindRotateArgs &a) {
 #pragma unroll
                 for (int o = 0; o < 2; ++o)
                     ahead[part][r][o] = load_key(
-                        key_rsrc, (uint32_t)(tid + (part >> 1) * kThreadsPerGate * B) * (uint32_t)sizeof(double2),
+                        key_rsrc, (uint32_t)(tid + (part >> 1) * TPG * B) * (uint32_t)sizeof(double2),
                         row_bytes + (uint32_t)((r * 4 + 2 * (part & 1) + o) * kHalf * sizeof(double2)));
     };
     if (AHEAD) load_ahead(0);
 
     int abar_next = my.bar[0];
     for (int i = 0; i < a.n; ++i) {
+        double2 x[8];
+        if (fft_wave) {
         // ---- rotate, subtract, decompose, fold and twist ----
         // read one step ahead (off the critical path); the same in every lane, so it goes to a scalar
         // register and the per-coefficient offsets below are scalar arithmetic
@@ -281,7 +288,6 @@ __device__ __forceinline__ void blind_rotate_body(const BlindRotateArgs &a) {
                 for (int h = 0; h < 2; ++h)
                     rot[m][h] = *(lds_word *)(uintptr_t)(((lane4 + shift4[m][h]) & 4092u) + acc_at);
         }
-        double2 x[8];
 #pragma unroll
         for (int m = 0; m < 8; ++m) {
             int32_t dig[2];
@@ -299,7 +305,8 @@ __device__ __forceinline__ void blind_rotate_body(const BlindRotateArgs &a) {
             }
             x[m] = make_double2((double)dig[0], (double)dig[1]);
         }
-        forward_to_slots(x, ln, my.spec[wv], L);
+        forward_to_slots(x, ln, my.spec[wv & 3], L);
+        }
         __syncthreads();
         // The short phase between the two barriers starts with the key loads: waves in it go first
         // (measured: 3 % faster than equal priorities; raising it in other phases loses).
@@ -311,8 +318,8 @@ __device__ __forceinline__ void blind_rotate_body(const BlindRotateArgs &a) {
             const uint32_t row_bytes = (uint32_t)i * 16u * kHalf * (uint32_t)sizeof(double2);
 #pragma unroll
             for (int pass = 0; pass < kSlotsPerThread; ++pass) {
-                const int s = tid + pass * kThreadsPerGate * B;
-                if (kThreadsPerGate * B * kSlotsPerThread != kHalf && s >= kHalf) break;
+                const int s = tid + pass * TPG * B;
+                if (TPG * B * kSlotsPerThread != kHalf && s >= kHalf) break;
                 const uint32_t voff = (uint32_t)s * (uint32_t)sizeof(double2);   // uniform base + 32-bit offset
                 double2 d[B][4];
 #pragma unroll
@@ -357,7 +364,8 @@ __device__ __forceinline__ void blind_rotate_body(const BlindRotateArgs &a) {
         abar_next = my.bar[i + 1];           // bar[n] exists (it holds bbar)
 
         // ---- inverse transform, exact rounding, accumulate ----
-        inverse_from_slots(x, ln, my.spec[wv], L);
+        if (fft_wave) {
+        inverse_from_slots(x, ln, my.spec[wv & 3], L);
 #pragma unroll
         for (int m = 0; m < 8; ++m) {
             const double part[2] = {x[m].x, x[m].y};
@@ -372,6 +380,7 @@ __device__ __forceinline__ void blind_rotate_body(const BlindRotateArgs &a) {
                 atomicAdd(&my.acc[comp][L + 64 * m + h * kHalf], r);
             }
         }
+        }
         __syncthreads();
     }
 
@@ -379,7 +388,7 @@ __device__ __forceinline__ void blind_rotate_body(const BlindRotateArgs &a) {
     if (live) {
         uint32_t *ext = a.ext + gi * (size_t)(kN + 1);
         // ACC = ~c, -ACC = c + 1
-        for (int j = lt; j < kN; j += kThreadsPerGate) ext[j] = j == 0 ? ~my.acc[0][0] : my.acc[0][kN - j] + 1u;
+        for (int j = lt; j < kN; j += TPG) ext[j] = j == 0 ? ~my.acc[0][0] : my.acc[0][kN - j] + 1u;
         if (lt == 0) ext[kN] = ~my.acc[1][0];
     }
     if (MARGIN) {
@@ -395,9 +404,10 @@ __global__ __launch_bounds__(kThreadsPerGate *B) __attribute__((amdgpu_waves_per
 }
 
 // The same step for batches of at most one gate per CU, where a gate's latency is all that counts.
+constexpr int kLatencyThreads = 512;
 template <bool MARGIN>
-__global__ __launch_bounds__(kThreadsPerGate) __attribute__((amdgpu_waves_per_eu(1, 1))) void blind_rotate_latency_kernel(BlindRotateArgs a) {
-    blind_rotate_body<1, MARGIN, 4>(a);
+__global__ __launch_bounds__(kLatencyThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void blind_rotate_latency_kernel(BlindRotateArgs a) {
+    blind_rotate_body<1, MARGIN, 2, kLatencyThreads>(a);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -810,9 +820,9 @@ static int launch_br_latency(const BlindRotateArgs &a, hipStream_t stream) {
     if (int rc = allow_dynamic_lds(reinterpret_cast<const void *>(&blind_rotate_latency_kernel<false>), lds, plain)) return rc;
     if (int rc = allow_dynamic_lds(reinterpret_cast<const void *>(&blind_rotate_latency_kernel<true>), lds, with_margin)) return rc;
     if (a.margin)
-        hipLaunchKernelGGL(blind_rotate_latency_kernel<true>, dim3((unsigned)a.count), dim3(kThreadsPerGate), lds, stream, a);
+        hipLaunchKernelGGL(blind_rotate_latency_kernel<true>, dim3((unsigned)a.count), dim3(kLatencyThreads), lds, stream, a);
     else
-        hipLaunchKernelGGL(blind_rotate_latency_kernel<false>, dim3((unsigned)a.count), dim3(kThreadsPerGate), lds, stream, a);
+        hipLaunchKernelGGL(blind_rotate_latency_kernel<false>, dim3((unsigned)a.count), dim3(kLatencyThreads), lds, stream, a);
     TFHE_HIP(hipGetLastError());
     return TFHE_OK;
 }
