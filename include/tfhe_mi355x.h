@@ -158,6 +158,22 @@ int tfhe_cloud_key_upload(tfhe_cloud_key *ck);
 int tfhe_gate_batch(tfhe_cloud_key *ck, int op, const uint32_t *a, const uint32_t *b,
                     uint32_t *out, size_t count, void *stream);
 
+/* For callers that cannot allocate (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc): tfhe_gate_batch with no allocation of any kind inside.
+ * The samples between the blind rotation and the key switch -- the one scratch buffer of
+ * this path, 4,100 B per gate -- live in a static device array of the library
+ * (TFHE_NOALLOC_MAX_GATES x 4,100 B = 16.8 MB per GPU, held until the process ends) instead of
+ * the cloud key's growing workspace.  Same arguments, results and aliasing rule as
+ * tfhe_gate_batch.  ck must already be uploaded (tfhe_cloud_key_upload, which allocates and
+ * looks the array's address up for its device) to the current device; otherwise TFHE_E_PARAM /
+ * TFHE_E_HIP.  count > TFHE_NOALLOC_MAX_GATES gives TFHE_E_SIZE and enqueues nothing.
+ * Profiling (tfhe_profile_enable) does not cover this call.  All calls on one GPU share the
+ * one array: calls that overlap in time on the same GPU (different streams, threads or cloud
+ * keys) race; successive calls on one stream do not. */
+#define TFHE_NOALLOC_MAX_GATES 4096
+int tfhe_gate_batch_noalloc(tfhe_cloud_key *ck, int op, const uint32_t *a, const uint32_t *b,
+                            uint32_t *out, size_t count, void *stream);
+
 /* count independent multiplexers: out[i] = s[i] ? a[i] : b[i].  All buffers DEVICE [count][n+1];
  * out may be the same buffer as s, a or b (exactly). */
 int tfhe_mux_batch(tfhe_cloud_key *ck, const uint32_t *s, const uint32_t *a, const uint32_t *b,

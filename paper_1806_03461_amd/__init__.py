@@ -44,6 +44,7 @@ class Profile(C.Structure):
 EXPORTS = ["tfhe_last_error", "tfhe_default_params", "tfhe_keygen", "tfhe_encrypt", "tfhe_decrypt",
            "tfhe_trivial", "tfhe_export_key", "tfhe_import_keys", "tfhe_get_params", "tfhe_free_secret_key",
            "tfhe_free_cloud_key", "tfhe_free_buffer", "tfhe_cloud_key_upload", "tfhe_gate_batch",
+           "tfhe_gate_batch_noalloc",
            "tfhe_mux_batch", "tfhe_gate_stream", "bnn_dense_lower", "bnn_dense_lower_opts", "bnn_conv_lower",
            "bnn_conv_lower_opts", "bnn_dense_encrypted", "bnn_dense_encrypted_opts", "bnn_conv_encrypted_opts",
            "bnn_conv_encrypted", "tfhe_profile_enable", "tfhe_profile_read",
@@ -78,6 +79,7 @@ def lib():
         L.tfhe_free_buffer.restype = None
         L.tfhe_cloud_key_upload.argtypes = [vp]
         L.tfhe_gate_batch.argtypes = [vp, i32, vp, vp, vp, sz, vp]
+        L.tfhe_gate_batch_noalloc.argtypes = [vp, i32, vp, vp, vp, sz, vp]
         L.tfhe_mux_batch.argtypes = [vp, vp, vp, vp, vp, sz, vp]
         L.tfhe_gate_stream.argtypes = [vp, vp, sz, vp, sz, vp]
         lower_tail = [C.POINTER(vp), C.POINTER(sz), C.POINTER(vp), C.POINTER(sz), C.POINTER(sz)]
@@ -217,6 +219,15 @@ def tfhe_cloud_key_upload(ck):
 def tfhe_gate_batch(ck, op, a, b, out, count, stream=None):
     op = OPS[op] if isinstance(op, str) else int(op)
     _check(lib().tfhe_gate_batch(ck.handle, op, _dev_ptr(a), _dev_ptr(b), _dev_ptr(out), count, _stream(stream)))
+
+
+NOALLOC_MAX_GATES = 4096
+
+
+def tfhe_gate_batch_noalloc(ck, op, a, b, out, count, stream=None):
+    op = OPS[op] if isinstance(op, str) else int(op)
+    _check(lib().tfhe_gate_batch_noalloc(ck.handle, op, _dev_ptr(a), _dev_ptr(b), _dev_ptr(out), count,
+                                         _stream(stream)))
 
 
 def tfhe_mux_batch(ck, s, a, b, out, count, stream=None):

@@ -152,13 +152,15 @@ int end_timed(tfhe_cloud_key *ck, hipStream_t stream, TimedLaunch &tl) {
 
 // One batch of `count` gates: blind rotation into the extract workspace, then key switch.
 // `count` counts launch items: a multiplexer is two of them (its two blind rotations).
+// `ext` is the [count][N+1] buffer of extracted samples between the two kernels (NULL: the
+// cloud key's workspace); with timed = false no event is created even in profiling mode.
 int run_batch(tfhe_cloud_key *ck, const tfhe_gate_rec *d_recs, int uniform_op, const uint32_t *in0,
               const uint32_t *in1, const uint32_t *in1_alt, uint32_t *out, size_t count, bool has_mux,
-              hipStream_t stream) {
+              hipStream_t stream, uint32_t *ext = nullptr, bool timed = true) {
     const tfhe_params &P = ck->params;
     BlindRotateArgs br{};
     br.recs = d_recs; br.uniform_op = uniform_op; br.in0 = in0; br.in1 = in1; br.in1_alt = in1_alt;
-    br.ext = (uint32_t *)ck->ws_ext.ptr; br.count = count;
+    br.ext = ext ? ext : (uint32_t *)ck->ws_ext.ptr; br.count = count;
     br.bk_fft = ck->d_bk_fft; br.tables = ck->d_tables; br.n = P.n; br.bgbit = P.bk_Bgbit;
     br.margin = ck->margin ? ck->d_margin : nullptr;
     KeySwitchArgs ks{};
@@ -178,14 +180,15 @@ int run_batch(tfhe_cloud_key *ck, const tfhe_gate_rec *d_recs, int uniform_op, c
     ks.uniform_mux = !d_recs && uniform_op == TFHE_MUX;
 
     TimedLaunch tl{};
-    if (ck->profile) if (int rc = begin_timed(ck, 0, stream, tl)) return rc;
+    const bool profile = ck->profile && timed;
+    if (profile) if (int rc = begin_timed(ck, 0, stream, tl)) return rc;
     if (int rc = launch_blind_rotate(br, gates_per_group(), stream)) return rc;
-    if (ck->profile) if (int rc = end_timed(ck, stream, tl)) return rc;
+    if (profile) if (int rc = end_timed(ck, stream, tl)) return rc;
     if (has_mux) if (int rc = launch_mux_combine(br.ext, d_recs, count, stream)) return rc;
-    if (ck->profile) if (int rc = begin_timed(ck, 1, stream, tl)) return rc;
+    if (profile) if (int rc = begin_timed(ck, 1, stream, tl)) return rc;
     if (int rc = launch_key_switch(ks, stream)) return rc;
-    if (ck->profile) if (int rc = end_timed(ck, stream, tl)) return rc;
-    if (ck->profile) ck->prof_gates += count;
+    if (profile) if (int rc = end_timed(ck, stream, tl)) return rc;
+    if (profile) ck->prof_gates += count;
     return TFHE_OK;
 }
 
@@ -343,6 +346,7 @@ static int tfhe_cloud_key_upload_impl(tfhe_cloud_key *ck) {
 
     TFHE_HIP(hipMalloc((void **)&ck->d_margin, sizeof(double)));
     TFHE_HIP(hipMemset(ck->d_margin, 0, sizeof(double)));
+    if (int rc = prepare_kernels()) return rc;
     ck->uploaded = true;
     return TFHE_OK;
 }
@@ -385,6 +389,30 @@ static int tfhe_gate_batch_impl(tfhe_cloud_key *ck, int op, const uint32_t *a, c
 int tfhe_gate_batch(tfhe_cloud_key *ck, int op, const uint32_t *a, const uint32_t *b, uint32_t *out,
                     size_t count, void *stream) {
     return tfhe::guarded([&]() -> int { return tfhe_gate_batch_impl(ck, op, a, b, out, count, stream); });
+}
+
+// The same gates with no allocation anywhere on the way: the samples between the two kernels go
+// to the device's static scratch array, whose address prepare_kernels() looked up at upload.
+static int tfhe_gate_batch_noalloc_impl(tfhe_cloud_key *ck, int op, const uint32_t *a, const uint32_t *b,
+                                        uint32_t *out, size_t count, void *stream) {
+    if (int rc = check_cloud_key(ck)) return rc;
+    if (!ck->uploaded)
+        return set_error(TFHE_E_PARAM, "tfhe_gate_batch_noalloc needs an uploaded cloud key "
+                                       "(call tfhe_cloud_key_upload first: the upload allocates)");
+    if (op < TFHE_NAND || op > TFHE_XNOR) return set_error(TFHE_E_PARAM, "unknown two-input gate opcode %d", op);
+    if (count > static_scratch_gates())
+        return set_error(TFHE_E_SIZE, "tfhe_gate_batch_noalloc takes at most %zu gates per call, got %zu",
+                         static_scratch_gates(), count);
+    if (count == 0) return TFHE_OK;
+    if (!a || !b || !out) return set_error(TFHE_E_NULL, "NULL ciphertext buffer");
+    uint32_t *ext = static_scratch_ptr();
+    if (!ext) return set_error(TFHE_E_HIP, "the cloud key was uploaded to another device than the current one");
+    return run_batch(ck, nullptr, op, a, b, nullptr, out, count, false, (hipStream_t)stream, ext, false);
+}
+
+int tfhe_gate_batch_noalloc(tfhe_cloud_key *ck, int op, const uint32_t *a, const uint32_t *b, uint32_t *out,
+                            size_t count, void *stream) {
+    return tfhe::guarded([&]() -> int { return tfhe_gate_batch_noalloc_impl(ck, op, a, b, out, count, stream); });
 }
 
 static int tfhe_mux_batch_impl(tfhe_cloud_key *ck, const uint32_t *s, const uint32_t *a, const uint32_t *b, uint32_t *out,

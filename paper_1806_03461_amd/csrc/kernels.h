@@ -45,6 +45,12 @@ int launch_ksk_to_tiles(const uint32_t *ksk, int stride, int words, void *tiles,
 int launch_mux_combine(uint32_t *ext, const tfhe_gate_rec *recs, size_t count, hipStream_t stream);
 int launch_gather_outputs(const uint32_t *wires, const tfhe_out_ref *refs, uint32_t *out, size_t count,
                           int words, hipStream_t stream);
+// per-device set-up at key upload: kernel attributes, address of the static scratch array
+int prepare_kernels();
+// the static scratch of the current device (NULL before prepare_kernels ran on it) and the
+// number of extracted samples ([1025] words each) it holds
+uint32_t *static_scratch_ptr();
+size_t static_scratch_gates();
 int launch_fill_trivial(uint32_t *ct, int words, int bit, hipStream_t stream);
 
 }  // namespace tfhe

@@ -790,6 +790,37 @@ static int allow_dynamic_lds(const void *kernel, size_t bytes, std::atomic<uint6
 
 size_t blind_rotate_lds_bytes(int gates_per_group) { return sizeof(GateLds) * (size_t)gates_per_group; }
 
+// ------------------------------------------------------------------------------------------
+// Scratch of the entry point that allocates nothing: the extracted samples between the blind
+// rotation and the key switch of at most kStaticGates gates.  Every device the library runs on
+// holds its own copy of the array at its own address, looked up once per device at key upload;
+// host code only ever uses that looked-up pointer, never the array's name.
+// ------------------------------------------------------------------------------------------
+constexpr size_t kStaticGates = TFHE_NOALLOC_MAX_GATES;
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) uint32_t scratch[kStaticGates * (kN + 1)];
+static std::atomic<uint32_t *> scratch_of_device[kMaxDevices];
+
+size_t static_scratch_gates() { return kStaticGates; }
+
+int static_scratch_init() {
+    int dev = 0;
+    TFHE_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return set_error(TFHE_E_HIP, "device index %d out of range", dev);
+    if (scratch_of_device[dev].load(std::memory_order_acquire)) return TFHE_OK;
+    uint32_t *ptr = nullptr;
+    TFHE_HIP(hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(scratch)));
+    if (!ptr) return set_error(TFHE_E_HIP, "no device address for the static scratch array");
+    scratch_of_device[dev].store(ptr, std::memory_order_release);
+    return TFHE_OK;
+}
+
+uint32_t *static_scratch_ptr() {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    return scratch_of_device[dev].load(std::memory_order_acquire);
+}
+
 int launch_bk_to_spectrum(const uint32_t *bk_raw, double2 *bk_fft, const double2 *tables, int n,
                           hipStream_t stream) {
     const unsigned blocks = (unsigned)n * 4 * 2 * 2;
@@ -836,6 +867,23 @@ int launch_blind_rotate(const BlindRotateArgs &a, int gates_per_group, hipStream
     case 3: return launch_br<3>(a, stream);
     default: return set_error(TFHE_E_PARAM, "unsupported gates per workgroup %d", gates_per_group);
     }
+}
+
+// Everything a launch would otherwise set up on first use (dynamic-LDS permissions, the cached
+// device properties), done once per device at key upload so that later calls only launch.
+int prepare_kernels() {
+    (void)latency_batch_limit();
+    const size_t lds = blind_rotate_lds_bytes(1);
+    static std::atomic<uint64_t> unused[6];
+    const void *kernels[6] = {reinterpret_cast<const void *>(&blind_rotate_kernel<1, false>),
+                              reinterpret_cast<const void *>(&blind_rotate_kernel<1, true>),
+                              reinterpret_cast<const void *>(&blind_rotate_latency_kernel<false>),
+                              reinterpret_cast<const void *>(&blind_rotate_latency_kernel<true>),
+                              reinterpret_cast<const void *>(&key_switch_mfma_kernel<false>),
+                              reinterpret_cast<const void *>(&key_switch_mfma_kernel<true>)};
+    for (int k = 0; k < 6; ++k)
+        if (int rc = allow_dynamic_lds(kernels[k], k < 4 ? lds : sizeof(KsMatrixLds), unused[k])) return rc;
+    return static_scratch_init();
 }
 
 int launch_ksk_to_tiles(const uint32_t *ksk, int stride, int words, void *tiles, hipStream_t stream) {

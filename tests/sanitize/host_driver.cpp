@@ -21,6 +21,9 @@ int launch_ksk_to_tiles(const uint32_t *, int, int, void *, hipStream_t) { retur
 int launch_mux_combine(uint32_t *, const tfhe_gate_rec *, size_t, hipStream_t) { return unreachable("mux"); }
 int launch_gather_outputs(const uint32_t *, const tfhe_out_ref *, uint32_t *, size_t, int, hipStream_t) { return unreachable("gather"); }
 int launch_fill_trivial(uint32_t *, int, int, hipStream_t) { return unreachable("fill"); }
+int prepare_kernels() { return unreachable("prepare"); }
+uint32_t *static_scratch_ptr() { return nullptr; }
+size_t static_scratch_gates() { return 4096; }
 }  // namespace tfhe
 
 #define CHECK(cond) do { if (!(cond)) { std::fprintf(stderr, "%s:%d: %s\n", __FILE__, __LINE__, #cond); return 1; } } while (0)
