@@ -32,8 +32,9 @@
  *     stream (the stream orders successive calls; calls on different streams would
  *     race on the workspaces).  An uploaded cloud key holds about 180 MB of device
  *     memory for the keys, up to 1.07 GB for the samples between the two kernels
- *     (4,100 B per gate of the widest launch) and, for the layer calls, one
- *     ciphertext (4 (n+1) bytes) per gate of the layer's circuit.
+ *     (4,100 B per gate of the widest launch) and, for the layer calls, a wire pool of
+ *     one ciphertext (4 (n+1) bytes) per wire that is alive at the same time (about a
+ *     third of the layer's gates; tfhe_last_layer_stats reports it).
  *   - The GPU path supports N = 1024, k = 1, bk_l = 2, bk_Bgbit <= 10, n <= 1024,
  *     ks_t * ks_basebit <= 24, ks_basebit <= 4; other parameters give TFHE_E_PARAM.
  */
@@ -261,13 +262,39 @@ int bnn_conv_encrypted(tfhe_cloud_key *ck, const uint32_t *x, int C, int H, int 
 /* Kernel-time accounting of server-side calls on a cloud key: when enabled, every blind
  * rotation and key-switch launch is bracketed by HIP events on the call's stream.
  * tfhe_profile_read synchronises the stream's events and returns accumulated milliseconds
- * and launch counts since the last reset. */
+ * and launch counts since the last reset.  Recording never waits for the device. */
 typedef struct {
     double blind_rotate_ms, key_switch_ms;
     uint64_t blind_rotate_launches, key_switch_launches, gates;
 } tfhe_profile;
 int tfhe_profile_enable(tfhe_cloud_key *ck, int on);
 int tfhe_profile_read(tfhe_cloud_key *ck, tfhe_profile *out, int reset);
+
+/* The schedule a layer call runs, as a host-side function: sort a lowered circuit by depth and
+ * rename its wires to slots of a pool in which a slot is reused once the last depth that reads
+ * its wire has run.  Wires 0 .. n_fixed-1 (inputs and the two constants) and the wires referenced
+ * by outs keep their slots; outs (HOST, nouts entries) is rewritten in place to slot numbers.
+ * *planned (release with tfhe_free_buffer) receives the ngates records in depth order with slot
+ * numbers: evaluating them in that order, depth by depth, on a pool of *pool_wires slots gives
+ * the circuit's outputs.  Same validation and errors as tfhe_gate_stream. */
+int tfhe_plan_wire_pool(const tfhe_gate_rec *gates, size_t ngates, size_t nwires, size_t n_fixed,
+                        tfhe_out_ref *outs, size_t nouts, tfhe_gate_rec **planned, size_t *pool_wires,
+                        size_t *depths);
+
+/* Shape of the circuit that the last bnn_*_encrypted call on this cloud key ran: gate records,
+ * wires of the lowered circuit (inputs, the two constants, one per gate), slots of the wire pool
+ * it was evaluated in (a slot is reused once the last depth reading its wire has run; this is
+ * the device memory the call needed, 4 (n+1) bytes per slot), and circuit depths (= kernel
+ * pairs when no depth is wider than a launch). */
+typedef struct {
+    uint64_t gates, circuit_wires, pool_wires, depths;
+} tfhe_layer_stats;
+int tfhe_last_layer_stats(const tfhe_cloud_key *ck, tfhe_layer_stats *out);
+
+/* Double-precision rate (TFLOP/s) that a register-resident FMA loop sustains on the key's device:
+ * the measured ceiling of the vector ALU that the blind rotation's transforms run on, to set
+ * beside the published peak.  Runs three short launches on `stream` and waits for them. */
+int tfhe_measure_fp64_peak(tfhe_cloud_key *ck, void *stream, double *tflops);
 
 /* Largest distance from an integer seen by the blind-rotation kernel when it rounds the
  * inverse transform of its exact split-integer products (0.5 would be a wrong result).

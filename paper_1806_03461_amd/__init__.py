@@ -41,13 +41,19 @@ class Profile(C.Structure):
                 ("gates", C.c_uint64)]
 
 
+class LayerStats(C.Structure):
+    _fields_ = [("gates", C.c_uint64), ("circuit_wires", C.c_uint64), ("pool_wires", C.c_uint64),
+                ("depths", C.c_uint64)]
+
+
 EXPORTS = ["tfhe_last_error", "tfhe_default_params", "tfhe_keygen", "tfhe_encrypt", "tfhe_decrypt",
            "tfhe_trivial", "tfhe_export_key", "tfhe_import_keys", "tfhe_get_params", "tfhe_free_secret_key",
            "tfhe_free_cloud_key", "tfhe_free_buffer", "tfhe_cloud_key_upload", "tfhe_gate_batch",
            "tfhe_gate_batch_noalloc",
            "tfhe_mux_batch", "tfhe_gate_stream", "bnn_dense_lower", "bnn_dense_lower_opts", "bnn_conv_lower",
            "bnn_conv_lower_opts", "bnn_dense_encrypted", "bnn_dense_encrypted_opts", "bnn_conv_encrypted_opts",
-           "bnn_conv_encrypted", "tfhe_profile_enable", "tfhe_profile_read",
+           "bnn_conv_encrypted", "tfhe_profile_enable", "tfhe_profile_read", "tfhe_last_layer_stats", "tfhe_plan_wire_pool",
+           "tfhe_measure_fp64_peak",
            "tfhe_rounding_margin_enable", "tfhe_rounding_margin_read"]
 
 _lib = None
@@ -92,6 +98,9 @@ def lib():
         L.bnn_conv_lower.argtypes = [i32, i32, i32, vp, i32, i32, i32, i32, i32, vp] + lower_tail
         L.bnn_dense_encrypted.argtypes = [vp, vp, i32, vp, vp, i32, vp, i32, vp]
         L.bnn_conv_encrypted.argtypes = [vp, vp, i32, i32, i32, vp, i32, i32, i32, i32, i32, vp, vp, vp]
+        L.tfhe_last_layer_stats.argtypes = [vp, C.POINTER(LayerStats)]
+        L.tfhe_plan_wire_pool.argtypes = [vp, sz, sz, sz, vp, sz, C.POINTER(vp), C.POINTER(sz), C.POINTER(sz)]
+        L.tfhe_measure_fp64_peak.argtypes = [vp, vp, C.POINTER(C.c_double)]
         L.tfhe_profile_enable.argtypes = [vp, i32]
         L.tfhe_profile_read.argtypes = [vp, C.POINTER(Profile), i32]
         L.tfhe_rounding_margin_enable.argtypes = [vp, i32]
@@ -325,6 +334,22 @@ def bnn_conv_encrypted(ck, x, C_, H, Wd, K, T, stride, pad, out, stream=None):
                                     T.ctypes.data, _dev_ptr(out), _stream(stream)))
 
 
+def tfhe_plan_wire_pool(gates, nwires, n_fixed, outs):
+    """Depth-sorted records in pool-slot numbers, the rewritten output references, pool size, depths."""
+    gates = _host(gates, GATE_DTYPE)
+    outs = np.array(outs, dtype=OUT_DTYPE, copy=True)
+    planned, pool, depths = C.c_void_p(), C.c_size_t(), C.c_size_t()
+    _check(lib().tfhe_plan_wire_pool(gates.ctypes.data, gates.size, nwires, n_fixed, outs.ctypes.data, outs.size,
+                                     C.byref(planned), C.byref(pool), C.byref(depths)))
+    return _take(planned, C.c_size_t(gates.size), GATE_DTYPE), outs, pool.value, depths.value
+
+
+def tfhe_last_layer_stats(ck):
+    st = LayerStats()
+    _check(lib().tfhe_last_layer_stats(ck.handle, C.byref(st)))
+    return {f: getattr(st, f) for f, _ in LayerStats._fields_}
+
+
 def tfhe_profile_enable(ck, on=True):
     _check(lib().tfhe_profile_enable(ck.handle, int(on)))
 
@@ -333,6 +358,12 @@ def tfhe_profile_read(ck, reset=True):
     p = Profile()
     _check(lib().tfhe_profile_read(ck.handle, C.byref(p), int(reset)))
     return {f: getattr(p, f) for f, _ in Profile._fields_}
+
+
+def tfhe_measure_fp64_peak(ck, stream=None):
+    v = C.c_double()
+    _check(lib().tfhe_measure_fp64_peak(ck.handle, _stream(stream), C.byref(v)))
+    return v.value
 
 
 def tfhe_rounding_margin_enable(ck, on=True):

@@ -11,6 +11,7 @@
 #include <algorithm>
 #include <cstdlib>
 #include <cstring>
+#include <functional>
 #include <new>
 #include <thread>
 
@@ -18,8 +19,9 @@
 #include "kernels.h"
 
 namespace tfhe {
-int run_gate_stream(tfhe_cloud_key *ck, const tfhe_gate_rec *gates, size_t ngates, uint32_t *wires,
-                    size_t nwires, hipStream_t stream);
+int run_layer_stream(tfhe_cloud_key *ck, const tfhe_gate_rec *gates, size_t ngates, size_t nwires, size_t n_fixed,
+                     std::vector<tfhe_out_ref> &outs, hipStream_t stream,
+                     const std::function<int(size_t pool_wires, uint32_t **wires)> &prepare);
 int ensure_uploaded(tfhe_cloud_key *ck);
 }
 
@@ -42,6 +44,9 @@ struct Number {
     int64_t bound = 0;
 };
 
+// wire numbers are int32: a circuit that would need more is refused before any record is handed out
+using WireOverflow = tfhe::CircuitTooLarge;
+
 class Builder {
 public:
     explicit Builder(int32_t n_inputs, bool share = false)
@@ -61,7 +66,7 @@ public:
         }
         tfhe_gate_rec r{};
         r.op = (uint8_t)op; r.neg0 = (uint8_t)a.flag; r.neg1 = (uint8_t)b.flag;
-        r.in0 = a.wire; r.in1 = b.wire; r.out = next_++;
+        r.in0 = a.wire; r.in1 = b.wire; r.out = take_wire();
         gates_.push_back(r);
         return Sig::of(r.out);
     }
@@ -70,7 +75,7 @@ public:
     Sig emit_mux(Sig sel, Sig a, Sig b) {
         tfhe_gate_rec r{};
         r.op = TFHE_MUX; r.neg0 = (uint8_t)sel.flag; r.neg1 = (uint8_t)a.flag;
-        r.in0 = sel.wire; r.in1 = a.wire; r.out = next_++;
+        r.in0 = sel.wire; r.in1 = a.wire; r.out = take_wire();
         gates_.push_back(r);
         r.op = TFHE_MUX_ELSE; r.neg1 = (uint8_t)b.flag; r.in1 = b.wire;
         gates_.push_back(r);
@@ -84,6 +89,7 @@ public:
     struct Slot { size_t gate_at; int32_t wire_shift; };
     Slot grow(const Builder &part) {
         const Slot s{gates_.size(), next_ - (zero_ + 2)};
+        if ((int64_t)next_ + (part.next_ - (zero_ + 2)) > (int64_t)INT32_MAX) throw WireOverflow();
         gates_.resize(gates_.size() + part.gates_.size());
         next_ += part.next_ - (zero_ + 2);
         return s;
@@ -303,6 +309,10 @@ public:
     }
 
 private:
+    int32_t take_wire() {
+        if (next_ == INT32_MAX) throw WireOverflow();
+        return next_++;
+    }
     std::vector<tfhe_gate_rec> gates_;
     int32_t next_, zero_, one_;
     bool share_;
@@ -376,7 +386,7 @@ int lower_units(int count, size_t work_per_unit, int32_t n_inputs, Builder &b, s
     struct Part {
         Builder b;
         std::vector<tfhe_out_ref> outs;
-        bool failed = false;
+        bool failed = false, overflow = false;
         explicit Part(int32_t n) : b(n) {}
     };
     std::vector<Part> parts;
@@ -390,13 +400,17 @@ int lower_units(int count, size_t work_per_unit, int32_t n_inputs, Builder &b, s
                 // about 7 gate records per input of a reduce-tree unit
                 parts[t].b.gates().reserve((size_t)(hi - lo) * work_per_unit * 7 + 64);
                 for (int j = lo; j < hi; ++j) per_unit(parts[t].b, parts[t].outs, j);
+            } catch (const WireOverflow &) {
+                parts[t].overflow = true;
             } catch (...) {
                 parts[t].failed = true;
             }
         });
     for (std::thread &th : pool) th.join();
-    for (Part &part : parts)
+    for (Part &part : parts) {
+        if (part.overflow) throw WireOverflow();
         if (part.failed) return set_error(TFHE_E_ALLOC, "out of host memory while lowering");
+    }
     std::vector<Builder::Slot> slots;
     for (Part &part : parts) slots.push_back(b.grow(part.b));
     pool.clear();
@@ -503,18 +517,24 @@ int lower_conv(int C, int H, int Wd, const int8_t *K, int O, int kh, int kw, int
     return TFHE_OK;
 }
 
-// wires = [inputs | noiseless 0 | noiseless 1 | gate outputs]; run; gather the outputs
-int evaluate(tfhe_cloud_key *ck, Builder &b, const std::vector<tfhe_out_ref> &outs, const uint32_t *x,
+// wire pool = [inputs | noiseless 0 | noiseless 1 | recycled slots of the gate outputs]; run; gather the outputs
+int evaluate(tfhe_cloud_key *ck, Builder &b, std::vector<tfhe_out_ref> &outs, const uint32_t *x,
              int n_inputs, uint32_t *out, hipStream_t stream) {
     const int words = ck->params.n + 1;
-    const size_t nwires = (size_t)b.wires();
-    if (int rc = ck->ws_wires.reserve(nwires * words * sizeof(uint32_t))) return rc;
+    uint32_t *wires = nullptr;
+    auto prepare = [&](size_t pool_wires, uint32_t **pool) -> int {
+        if (int rc = ck->ws_wires.reserve(pool_wires * words * sizeof(uint32_t))) return rc;
+        wires = (uint32_t *)ck->ws_wires.ptr;
+        TFHE_HIP(hipMemcpyAsync(wires, x, (size_t)n_inputs * words * sizeof(uint32_t), hipMemcpyDeviceToDevice, stream));
+        if (int rc = tfhe::launch_fill_trivial(wires + (size_t)n_inputs * words, words, 0, stream)) return rc;
+        if (int rc = tfhe::launch_fill_trivial(wires + (size_t)(n_inputs + 1) * words, words, 1, stream)) return rc;
+        *pool = wires;
+        return TFHE_OK;
+    };
+    if (int rc = tfhe::run_layer_stream(ck, b.gates().data(), b.gates().size(), (size_t)b.wires(), (size_t)n_inputs + 2,
+                                        outs, stream, prepare))
+        return rc;
     if (int rc = ck->ws_outs.reserve(std::max<size_t>(1, outs.size()) * sizeof(tfhe_out_ref))) return rc;
-    uint32_t *wires = (uint32_t *)ck->ws_wires.ptr;
-    TFHE_HIP(hipMemcpyAsync(wires, x, (size_t)n_inputs * words * sizeof(uint32_t), hipMemcpyDeviceToDevice, stream));
-    if (int rc = tfhe::launch_fill_trivial(wires + (size_t)n_inputs * words, words, 0, stream)) return rc;
-    if (int rc = tfhe::launch_fill_trivial(wires + (size_t)(n_inputs + 1) * words, words, 1, stream)) return rc;
-    if (int rc = tfhe::run_gate_stream(ck, b.gates().data(), b.gates().size(), wires, nwires, stream)) return rc;
     // the output references go through pinned staging as well: no host wait
     if (int rc = ck->stage_outs.reserve(std::max<size_t>(1, outs.size()) * sizeof(tfhe_out_ref))) return rc;
     if (!outs.empty()) memcpy(ck->stage_outs.ptr, outs.data(), outs.size() * sizeof(tfhe_out_ref));

@@ -23,11 +23,16 @@ int set_error(int code, const char *fmt, ...);
                                    hipGetErrorString(e_), __FILE__, __LINE__);              \
     } while (0)
 
+// thrown by the lowering when wire numbers would leave int32
+struct CircuitTooLarge {};
+
 // Runs an entry point's body: no C++ exception leaves the C ABI.
 template <class F>
 int guarded(F &&body) {
     try {
         return body();
+    } catch (const CircuitTooLarge &) {
+        return set_error(TFHE_E_SIZE, "the circuit needs more than 2^31 - 1 wires");
     } catch (const std::bad_alloc &) {
         return set_error(TFHE_E_ALLOC, "out of host memory");
     } catch (const std::exception &e) {
@@ -102,6 +107,8 @@ struct tfhe_cloud_key {
     uint64_t prof_gates = 0;
     bool margin = false;
     double *d_margin = nullptr;
+    // the last layer call: records, wires of its circuit, slots of the wire pool it ran in, depths
+    size_t last_layer_gates = 0, last_layer_wires = 0, last_layer_pool = 0, last_layer_levels = 0;
 };
 
 #define TFHE_SK_MAGIC 0x53454b31u

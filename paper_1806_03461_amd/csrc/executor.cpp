@@ -9,6 +9,7 @@
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
+#include <functional>
 #include <new>
 
 #include "common.h"
@@ -84,24 +85,6 @@ size_t chunk_gates() {
     return cached;
 }
 
-int gates_per_group() {
-    static const int cached = [] {
-        const long v = env_long("TFHE_GATES_PER_GROUP", 1);
-        return (v >= 1 && v <= 3) ? (int)v : 1;
-    }();
-    return cached;
-}
-
-// Gates per key-switch workgroup: large batches amortise the 49 MB key over 16 gates; small
-// batches (the deep, narrow levels of a circuit) need many short workgroups instead.
-int key_switch_group(size_t count) {
-    static const int forced = (int)env_long("TFHE_KS_GROUP", 0);
-    if (forced > 0) return forced;
-    if (count >= 8192) return 16;
-    if (count >= 2048) return 4;
-    return 1;
-}
-
 // Batches from which the key switch runs as an int8 contraction on the matrix cores: all of them
 // (small batches split each gate's mask words over several workgroups; 16 gates take 0.035 ms
 // against 0.086 ms of the gather kernels, 256 gates 0.065 against 0.42 ms).  The gather kernels
@@ -144,9 +127,21 @@ int drain_timed(tfhe_cloud_key *ck) {
 int end_timed(tfhe_cloud_key *ck, hipStream_t stream, TimedLaunch &tl) {
     TFHE_HIP(hipEventRecord(tl.stop, stream));
     ck->timed.push_back(tl);
-    // a caller that never reads the profile must not pile up events: fold them in now and then
-    // (this waits for the launches so far; profiling is a measurement mode)
-    if (ck->timed.size() >= 4096) return drain_timed(ck);
+    // a caller that never reads the profile must not pile up events: now and then fold in the
+    // pairs that have already finished, without waiting for any that have not
+    if (ck->timed.size() >= 4096 && ck->timed.size() % 1024 == 0) {
+        size_t done = 0;
+        while (done < ck->timed.size() && hipEventQuery(ck->timed[done].stop) == hipSuccess) {
+            float ms = 0;
+            TFHE_HIP(hipEventElapsedTime(&ms, ck->timed[done].start, ck->timed[done].stop));
+            ck->prof_ms[ck->timed[done].kind] += ms;
+            ck->prof_launches[ck->timed[done].kind] += 1;
+            (void)hipEventDestroy(ck->timed[done].start);
+            (void)hipEventDestroy(ck->timed[done].stop);
+            ++done;
+        }
+        ck->timed.erase(ck->timed.begin(), ck->timed.begin() + (std::ptrdiff_t)done);
+    }
     return TFHE_OK;
 }
 
@@ -166,13 +161,12 @@ int run_batch(tfhe_cloud_key *ck, const tfhe_gate_rec *d_recs, int uniform_op, c
     KeySwitchArgs ks{};
     ks.ext = br.ext; ks.recs = d_recs; ks.out = out; ks.count = count; ks.ksk = ck->d_ksk;
     ks.n = P.n; ks.t = P.ks_t; ks.basebit = P.ks_basebit; ks.stride = (P.n + 2) & ~1;
-    ks.group = key_switch_group(count);
     ks.ksk_tiles = ck->d_ksk_tiles;
     ks.matrix = key_switch_matrix(count);
     // few gates (the deep, narrow levels of a circuit): spread each gate over several
     // workgroups so that the whole chip works on the batch
     ks.splits = 1;
-    if (ks.group == 1) {
+    {
         static const int forced = (int)env_long("TFHE_KS_SPLITS", 0);
         if (forced > 0) ks.splits = forced;
         else while (ks.splits < 16 && count * ks.splits < 4096) ks.splits *= 2;
@@ -182,7 +176,7 @@ int run_batch(tfhe_cloud_key *ck, const tfhe_gate_rec *d_recs, int uniform_op, c
     TimedLaunch tl{};
     const bool profile = ck->profile && timed;
     if (profile) if (int rc = begin_timed(ck, 0, stream, tl)) return rc;
-    if (int rc = launch_blind_rotate(br, gates_per_group(), stream)) return rc;
+    if (int rc = launch_blind_rotate(br, stream)) return rc;
     if (profile) if (int rc = end_timed(ck, stream, tl)) return rc;
     if (has_mux) if (int rc = launch_mux_combine(br.ext, d_recs, count, stream)) return rc;
     if (profile) if (int rc = begin_timed(ck, 1, stream, tl)) return rc;
@@ -194,10 +188,17 @@ int run_batch(tfhe_cloud_key *ck, const tfhe_gate_rec *d_recs, int uniform_op, c
 
 }  // namespace
 
-// Evaluate host gate records (validated, any order within the topological constraint) on device wires.
-int run_gate_stream(tfhe_cloud_key *ck, const tfhe_gate_rec *gates, size_t ngates, uint32_t *wires,
-                    size_t nwires, hipStream_t stream) {
-    if (ngates == 0) return TFHE_OK;
+namespace {
+
+// Validation and ASAP levels of a topologically ordered gate list.
+struct Levels {
+    std::vector<int32_t> level;     // per record
+    std::vector<size_t> start;      // records of level l occupy sorted positions [start[l], start[l+1])
+    int32_t max_level = 0;
+    bool any_mux = false;
+};
+
+int levelize(const tfhe_gate_rec *gates, size_t ngates, size_t nwires, Levels &lv) {
     if (ngates > (size_t)INT32_MAX || nwires > (size_t)INT32_MAX)
         return set_error(TFHE_E_SIZE, "too many gates or wires");
     // writer of each wire; an input must be produced by an earlier record or by nobody.  The
@@ -223,57 +224,162 @@ int run_gate_stream(tfhe_cloud_key *ck, const tfhe_gate_rec *gates, size_t ngate
         if (writer[r.out] >= 0) return set_error(TFHE_E_PARAM, "gate %zu: wire %d written twice", g, r.out);
         writer[r.out] = (int32_t)g;
     }
-    std::vector<int32_t> level(ngates);
+    lv.level.assign(ngates, 0);
     std::vector<int32_t> depth(nwires, 0);
-    int32_t max_level = 0;
-    bool any_mux = false;
+    lv.max_level = 0;
+    lv.any_mux = false;
     for (size_t g = 0; g < ngates; ++g) {
         const tfhe_gate_rec &r = gates[g];
-        if (r.op == TFHE_MUX_ELSE) { level[g] = level[g - 1]; continue; }
+        if (r.op == TFHE_MUX_ELSE) { lv.level[g] = lv.level[g - 1]; continue; }
         const int32_t self = (int32_t)g;
         if (writer[r.in0] >= self || writer[r.in1] >= self)
             return set_error(TFHE_E_PARAM, "gate %zu reads a wire written by itself or a later record", g);
-        int32_t lv = 1 + std::max(depth[r.in0], depth[r.in1]);
+        int32_t l = 1 + std::max(depth[r.in0], depth[r.in1]);
         if (r.op == TFHE_MUX) {
-            any_mux = true;
+            lv.any_mux = true;
             if (writer[gates[g + 1].in1] >= self)
                 return set_error(TFHE_E_PARAM, "gate %zu reads a wire written by itself or a later record", g + 1);
-            lv = std::max(lv, 1 + depth[gates[g + 1].in1]);
+            l = std::max(l, 1 + depth[gates[g + 1].in1]);
         }
-        level[g] = lv;
-        depth[r.out] = lv;
-        max_level = std::max(max_level, lv);
+        lv.level[g] = l;
+        depth[r.out] = l;
+        lv.max_level = std::max(lv.max_level, l);
     }
     // counting sort by depth
-    std::vector<size_t> start(max_level + 2, 0);
-    for (size_t g = 0; g < ngates; ++g) ++start[level[g] + 1];
-    for (int32_t l = 1; l <= max_level + 1; ++l) start[l] += start[l - 1];
-    // sorted records go through a pinned staging buffer: the upload is ordered on the stream and
-    // the call does not wait for it (nor for anything queued before it)
-    if (int rc = ck->stage_gates.reserve(ngates * sizeof(tfhe_gate_rec))) return rc;
-    tfhe_gate_rec *sorted = (tfhe_gate_rec *)ck->stage_gates.ptr;
-    {
-        std::vector<size_t> at(start.begin(), start.end());
-        for (size_t g = 0; g < ngates; ++g) sorted[at[level[g]]++] = gates[g];
-    }
+    lv.start.assign((size_t)lv.max_level + 2, 0);
+    for (size_t g = 0; g < ngates; ++g) ++lv.start[(size_t)lv.level[g] + 1];
+    for (int32_t l = 1; l <= lv.max_level + 1; ++l) lv.start[l] += lv.start[l - 1];
+    return TFHE_OK;
+}
+
+// The depth-sorted records already sit in the pinned staging buffer: upload them and run one
+// kernel pair per depth (in chunks) on the stream.  The upload is ordered on the stream and the
+// call does not wait for it (nor for anything queued before it).
+int launch_levels(tfhe_cloud_key *ck, size_t ngates, const Levels &lv, uint32_t *wires, hipStream_t stream) {
+    const tfhe_gate_rec *sorted = (const tfhe_gate_rec *)ck->stage_gates.ptr;
     if (int rc = ck->ws_gates.reserve(ngates * sizeof(tfhe_gate_rec))) return rc;
     const size_t kChunkGates = chunk_gates();
     size_t biggest = 0;
-    for (int32_t l = 1; l <= max_level; ++l) biggest = std::max(biggest, std::min(kChunkGates, start[l + 1] - start[l]));
+    for (int32_t l = 1; l <= lv.max_level; ++l)
+        biggest = std::max(biggest, std::min(kChunkGates, lv.start[l + 1] - lv.start[l]));
     if (int rc = ck->ws_ext.reserve(biggest * (size_t)(ck->params.N + 1) * sizeof(uint32_t))) return rc;
     TFHE_HIP(hipMemcpyAsync(ck->ws_gates.ptr, sorted, ngates * sizeof(tfhe_gate_rec), hipMemcpyHostToDevice,
                             stream));
     if (int rc = ck->stage_gates.mark(stream)) return rc;
     const tfhe_gate_rec *d_recs = (const tfhe_gate_rec *)ck->ws_gates.ptr;
-    for (int32_t l = 1; l <= max_level; ++l) {
-        for (size_t at = start[l]; at < start[l + 1];) {
-            size_t cnt = std::min(kChunkGates, start[l + 1] - at);
+    for (int32_t l = 1; l <= lv.max_level; ++l) {
+        for (size_t at = lv.start[l]; at < lv.start[l + 1];) {
+            size_t cnt = std::min(kChunkGates, lv.start[l + 1] - at);
             if (sorted[at + cnt - 1].op == TFHE_MUX) --cnt;      // keep the two halves in one batch
-            if (int rc = run_batch(ck, d_recs + at, 0, wires, wires, wires, wires, cnt, any_mux, stream)) return rc;
+            if (int rc = run_batch(ck, d_recs + at, 0, wires, wires, wires, wires, cnt, lv.any_mux, stream)) return rc;
             at += cnt;
         }
     }
     return TFHE_OK;
+}
+
+}  // namespace
+
+// Evaluate host gate records (validated, any order within the topological constraint) on device
+// wires that the caller owns: every wire keeps the index the records give it.
+int run_gate_stream(tfhe_cloud_key *ck, const tfhe_gate_rec *gates, size_t ngates, uint32_t *wires,
+                    size_t nwires, hipStream_t stream) {
+    if (ngates == 0) return TFHE_OK;
+    Levels lv;
+    if (int rc = levelize(gates, ngates, nwires, lv)) return rc;
+    if (int rc = ck->stage_gates.reserve(ngates * sizeof(tfhe_gate_rec))) return rc;
+    tfhe_gate_rec *sorted = (tfhe_gate_rec *)ck->stage_gates.ptr;
+    {
+        std::vector<size_t> at(lv.start.begin(), lv.start.end());
+        for (size_t g = 0; g < ngates; ++g) sorted[at[lv.level[g]]++] = gates[g];
+    }
+    return launch_levels(ck, ngates, lv, wires, stream);
+}
+
+// Rename the wires of a levelized circuit to slots of a pool: a slot is handed out again once the
+// last depth that reads its wire has run (a depth's kernels follow the previous depth's on the
+// stream, and a slot freed by depth l is first written by depth l + 1).  Wires 0 .. n_fixed-1
+// (a layer's inputs and the two constants) and the wires that `outs` references keep their slots
+// to the end.  `sorted` receives the depth-sorted records in slot numbers, `outs` is rewritten
+// to slots, *pool_wires is the number of slots used.
+int plan_wire_pool(const tfhe_gate_rec *gates, size_t ngates, size_t nwires, size_t n_fixed, const Levels &lv,
+                   tfhe_gate_rec *sorted, tfhe_out_ref *outs, size_t nouts, size_t *pool_wires) {
+    size_t pool = n_fixed;
+    // last depth that reads each wire (its own depth if nothing reads it); outputs never expire
+    std::vector<int32_t> last(nwires, 0);
+    for (size_t g = 0; g < ngates; ++g) {
+        const tfhe_gate_rec &r = gates[g];
+        const int32_t l = lv.level[g];
+        last[r.in0] = std::max(last[r.in0], l);
+        last[r.in1] = std::max(last[r.in1], l);
+        last[r.out] = std::max(last[r.out], l);
+    }
+    for (size_t k = 0; k < nouts; ++k) {
+        if (outs[k].wire >= (int64_t)nwires) return set_error(TFHE_E_SIZE, "output %zu: wire index out of range", k);
+        if (outs[k].wire >= 0) last[outs[k].wire] = INT32_MAX;
+    }
+    {
+        std::vector<size_t> at(lv.start.begin(), lv.start.end());
+        for (size_t g = 0; g < ngates; ++g) sorted[at[lv.level[g]]++] = gates[g];
+    }
+    std::vector<int32_t> slot(nwires, -1);
+    for (size_t w = 0; w < n_fixed && w < nwires; ++w) slot[w] = (int32_t)w;
+    std::vector<int32_t> free_slots;
+    auto expire = [&](int32_t w, int32_t l) {
+        if ((size_t)w >= n_fixed && last[w] == l) { free_slots.push_back(slot[w]); last[w] = -1; }
+    };
+    for (int32_t l = 1; l <= lv.max_level; ++l) {
+        const size_t lo = lv.start[l], hi = lv.start[l + 1];
+        for (size_t g = lo; g < hi; ++g) {               // outputs of this depth take slots
+            const tfhe_gate_rec &r = sorted[g];
+            if (r.op == TFHE_MUX_ELSE) continue;           // shares the output of the record before it
+            if ((size_t)r.out < n_fixed) return set_error(TFHE_E_PARAM, "a gate writes a fixed wire");
+            if (free_slots.empty()) slot[r.out] = (int32_t)pool++;
+            else { slot[r.out] = free_slots.back(); free_slots.pop_back(); }
+        }
+        for (size_t g = lo; g < hi; ++g) {               // slots freed here serve depth l + 1 onwards
+            tfhe_gate_rec &r = sorted[g];
+            const int32_t in0 = r.in0, in1 = r.in1, out = r.out;
+            if (slot[in0] < 0 || slot[in1] < 0)
+                return set_error(TFHE_E_PARAM, "a gate reads a wire that is neither fixed nor written");
+            r.in0 = slot[in0]; r.in1 = slot[in1]; r.out = slot[out];
+            expire(in0, l); expire(in1, l);
+            if (r.op != TFHE_MUX) expire(out, l);           // a multiplexer's output expires with its second record
+        }
+        if (pool > (size_t)INT32_MAX) return set_error(TFHE_E_SIZE, "wire pool too large");
+    }
+    for (size_t k = 0; k < nouts; ++k)
+        if (outs[k].wire >= 0) {
+            if (slot[outs[k].wire] < 0) return set_error(TFHE_E_PARAM, "output %zu references a wire that is never written", k);
+            outs[k].wire = slot[outs[k].wire];
+        }
+    *pool_wires = pool;
+    return TFHE_OK;
+}
+
+// A layer's circuit on a wire pool the library owns.  `prepare` is called with the pool's size
+// (to allocate it and fill its fixed wires) before anything is launched; afterwards `outs`
+// refers to slots.
+int run_layer_stream(tfhe_cloud_key *ck, const tfhe_gate_rec *gates, size_t ngates, size_t nwires, size_t n_fixed,
+                     std::vector<tfhe_out_ref> &outs, hipStream_t stream,
+                     const std::function<int(size_t pool_wires, uint32_t **wires)> &prepare) {
+    Levels lv;
+    size_t pool = n_fixed;
+    if (ngates) {
+        if (int rc = levelize(gates, ngates, nwires, lv)) return rc;
+        if (int rc = ck->stage_gates.reserve(ngates * sizeof(tfhe_gate_rec))) return rc;
+        if (int rc = plan_wire_pool(gates, ngates, nwires, n_fixed, lv, (tfhe_gate_rec *)ck->stage_gates.ptr, outs.data(),
+                                    outs.size(), &pool))
+            return rc;
+    }
+    ck->last_layer_gates = ngates;
+    ck->last_layer_wires = nwires;
+    ck->last_layer_pool = pool;
+    ck->last_layer_levels = (size_t)lv.max_level;
+    uint32_t *wires = nullptr;
+    if (int rc = prepare(pool, &wires)) return rc;
+    if (ngates == 0) return TFHE_OK;
+    return launch_levels(ck, ngates, lv, wires, stream);
 }
 
 void release_device_keys(tfhe_cloud_key *ck) {
@@ -451,6 +557,42 @@ int tfhe_gate_stream(tfhe_cloud_key *ck, const tfhe_gate_rec *gates, size_t ngat
     return tfhe::guarded([&]() -> int { return tfhe_gate_stream_impl(ck, gates, ngates, wires, nwires, stream); });
 }
 
+static int tfhe_plan_wire_pool_impl(const tfhe_gate_rec *gates, size_t ngates, size_t nwires, size_t n_fixed,
+                                    tfhe_out_ref *outs, size_t nouts, tfhe_gate_rec **planned, size_t *pool_wires,
+                                    size_t *depths) {
+    if (!planned || !pool_wires || !depths) return set_error(TFHE_E_NULL, "NULL output pointer");
+    if ((ngates && !gates) || (nouts && !outs)) return set_error(TFHE_E_NULL, "NULL gates or outputs");
+    if (n_fixed > nwires) return set_error(TFHE_E_SIZE, "more fixed wires than wires");
+    Levels lv;
+    *planned = (tfhe_gate_rec *)malloc(std::max<size_t>(1, ngates) * sizeof(tfhe_gate_rec));
+    if (!*planned) return set_error(TFHE_E_ALLOC, "out of memory");
+    *pool_wires = n_fixed;
+    *depths = 0;
+    if (ngates == 0) return TFHE_OK;
+    int rc = levelize(gates, ngates, nwires, lv);
+    if (!rc) rc = plan_wire_pool(gates, ngates, nwires, n_fixed, lv, *planned, outs, nouts, pool_wires);
+    if (rc) { free(*planned); *planned = nullptr; return rc; }
+    *depths = (size_t)lv.max_level;
+    return TFHE_OK;
+}
+
+int tfhe_plan_wire_pool(const tfhe_gate_rec *gates, size_t ngates, size_t nwires, size_t n_fixed, tfhe_out_ref *outs,
+                        size_t nouts, tfhe_gate_rec **planned, size_t *pool_wires, size_t *depths) {
+    return tfhe::guarded([&]() -> int {
+        return tfhe_plan_wire_pool_impl(gates, ngates, nwires, n_fixed, outs, nouts, planned, pool_wires, depths);
+    });
+}
+
+int tfhe_last_layer_stats(const tfhe_cloud_key *ck, tfhe_layer_stats *out) {
+    if (!ck || ck->magic != TFHE_CK_MAGIC) return set_error(TFHE_E_NULL, "not a cloud key");
+    if (!out) return set_error(TFHE_E_NULL, "NULL output");
+    out->gates = ck->last_layer_gates;
+    out->circuit_wires = ck->last_layer_wires;
+    out->pool_wires = ck->last_layer_pool;
+    out->depths = ck->last_layer_levels;
+    return TFHE_OK;
+}
+
 int tfhe_profile_enable(tfhe_cloud_key *ck, int on) {
     if (int rc = check_cloud_key(ck)) return rc;
     ck->profile = on != 0;
@@ -476,6 +618,14 @@ static int tfhe_profile_read_impl(tfhe_cloud_key *ck, tfhe_profile *out, int res
 
 int tfhe_profile_read(tfhe_cloud_key *ck, tfhe_profile *out, int reset) {
     return tfhe::guarded([&]() -> int { return tfhe_profile_read_impl(ck, out, reset); });
+}
+
+int tfhe_measure_fp64_peak(tfhe_cloud_key *ck, void *stream, double *tflops) {
+    return tfhe::guarded([&]() -> int {
+        if (int rc = ensure_uploaded(ck)) return rc;
+        if (!tflops) return set_error(TFHE_E_NULL, "NULL output");
+        return measure_fp64_fma_peak((hipStream_t)stream, ck->d_margin, tflops);
+    });
 }
 
 int tfhe_rounding_margin_enable(tfhe_cloud_key *ck, int on) {

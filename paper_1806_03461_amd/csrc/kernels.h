@@ -26,17 +26,16 @@ struct KeySwitchArgs {
     const uint32_t *ksk;         // device [1024][t][2^basebit - 1][stride] plus one zero row
     int n, t, basebit;
     int uniform_mux;             // recs == NULL: items come in pairs, item 2g carries the sum and writes out[g]
-    int splits;                  // group == 1 only: workgroups sharing one gate's mask words (power of two)
-    int group;                   // gates sharing one pass over the key (1 = one gate per workgroup)
+    int splits;                  // gather kernel: workgroups sharing one gate's mask words (power of two)
     int stride;                  // words per key row on the device: n+1 rounded up to even, pad = 0
     const void *ksk_tiles;       // device, optional: the key as signed-byte tiles for the matrix-core kernel
     int matrix;                  // use the matrix-core kernel (needs ksk_tiles, t = 8, basebit = 2, n + 1 <= 512)
 };
 
-size_t blind_rotate_lds_bytes(int gates_per_group);
+size_t blind_rotate_lds_bytes();
 int launch_bk_to_spectrum(const uint32_t *bk_raw, double2 *bk_fft, const double2 *tables, int n,
                           hipStream_t stream);
-int launch_blind_rotate(const BlindRotateArgs &a, int gates_per_group, hipStream_t stream);
+int launch_blind_rotate(const BlindRotateArgs &a, hipStream_t stream);
 int launch_key_switch(const KeySwitchArgs &a, hipStream_t stream);
 // the key-switching key (device, padded rows) as int8 operand tiles; `tiles` holds ksk_tiles_bytes()
 size_t ksk_tiles_bytes();
@@ -51,6 +50,8 @@ int prepare_kernels();
 // number of extracted samples ([1025] words each) it holds
 uint32_t *static_scratch_ptr();
 size_t static_scratch_gates();
+// achieved TFLOP/s of a register-resident FP64 FMA loop on the current device (synchronises `stream`)
+int measure_fp64_fma_peak(hipStream_t stream, double *sink, double *tflops);
 int launch_fill_trivial(uint32_t *ct, int words, int bit, hipStream_t stream);
 
 }  // namespace tfhe

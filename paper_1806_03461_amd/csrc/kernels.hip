@@ -14,6 +14,7 @@
 // makes this cheaper than any 32-bit-integer number-theoretic transform on its VALU.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <atomic>
 #include <cstddef>
 #include <cstdlib>
@@ -39,50 +40,20 @@ __device__ __forceinline__ void wave_sync() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-// Forward transform of the 8 folded points held in x; leaves the spectrum in buf in
-// slot order (slot = 64 * register + lane).
-__device__ __forceinline__ void forward_to_slots(double2 (&x)[8], const Lane &ln, double2 *buf, int L) {
-    fwd_pass1_store(x, ln, buf, L);
-    wave_sync();
-    fwd_pass2_load(x, buf, L);
-    wave_sync();
-    fwd_pass2_store(x, ln, buf, L);
-    wave_sync();
-    fwd_pass3(x, buf, L);
-    wave_sync();
-#pragma unroll
-    for (int k = 0; k < 8; ++k) buf[k * 64 + L] = x[k];
-}
-
-// Inverse transform of the spectrum held in buf (slot order); x[m] is 512 times the folded
-// point L + 64 m (real part: coefficient L + 64 m, imaginary part: coefficient L + 64 m + 512).
-__device__ __forceinline__ void inverse_from_slots(double2 (&x)[8], const Lane &ln, double2 *buf, int L) {
-#pragma unroll
-    for (int k = 0; k < 8; ++k) x[k] = buf[k * 64 + L];
-    wave_sync();
-    inv_pass3_store(x, ln, buf, L);
-    wave_sync();
-    inv_pass2(x, buf, L);
-    wave_sync();
-    inv_pass2_store(x, buf, L);
-    wave_sync();
-    inv_pass1(x, ln, buf, L);
-}
-
 // ------------------------------------------------------------------------------------------
-// Bootstrapping key -> transform domain.  One wave per (sample row, component, limb).
-// bk_raw [n][4][2][1024] uint32  ->  bk_fft [n][4][o = 2*component + limb][512] complex.
+// Bootstrapping key -> transform domain.  One workgroup per sample row (i, r): its four waves
+// transform the four polynomials o = 2*component + limb with the very steps the blind rotation
+// applies to its four digit polynomials, so the spectra land in the slot order the products use.
+// bk_raw [n][4][2][1024] uint32  ->  bk_fft [n][4][o][512] complex.
 // ------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(64) void bk_to_spectrum_kernel(const uint32_t *__restrict__ bk_raw,
-                                                            double2 *__restrict__ bk_fft,
-                                                            const double2 *__restrict__ tables) {
+__global__ __launch_bounds__(256) void bk_to_spectrum_kernel(const uint32_t *__restrict__ bk_raw,
+                                                             double2 *__restrict__ bk_fft,
+                                                             const double2 *__restrict__ tables) {
     __shared__ double2 buf[kBufWords];
-    const int L = threadIdx.x;
-    const int limb = blockIdx.x & 1;
-    const size_t poly = blockIdx.x >> 1;           // (i * 4 + r) * 2 + c
-    const int c = (int)(poly & 1);
-    const size_t row = poly >> 1;                  // i * 4 + r
-    const uint32_t *src = bk_raw + poly * kN;
+    const int L = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const size_t row = blockIdx.x;                 // i * 4 + r
+    const int c = wv >> 1, limb = wv & 1;          // pass 1: wave o = 2 c + limb
+    const uint32_t *src = bk_raw + (row * 2 + (size_t)c) * kN;
     Lane ln;
     lane_init(ln, tables, L);
     double2 x[8];
@@ -100,28 +71,44 @@ __global__ __launch_bounds__(64) void bk_to_spectrum_kernel(const uint32_t *__re
         // the 1/512 of the inverse transform is folded into the key (exact: a power of two)
         x[m] = make_double2((double)v[0] * (1.0 / 512.0), (double)v[1] * (1.0 / 512.0));
     }
-    forward_to_slots(x, ln, buf, L);
+    fwd_pass1_store(x, ln, buf + wv * kPolyStride, L);
+    __syncthreads();
+    double2 *mine = buf + row_of(wv, L);
+    fwd_pass2_load(x, mine, L);
     wave_sync();
-    double2 *dst = bk_fft + (row * 4 + (size_t)(c * 2 + limb)) * kHalf;
+    fwd_pass2_store(x, ln, mine, L);
+    wave_sync();
+    fwd_pass3(x, mine, L);
+    gather_rows(x);
 #pragma unroll
-    for (int k = 0; k < 8; ++k) dst[k * 64 + L] = buf[k * 64 + L];
+    for (int o = 0; o < 4; ++o)
+#pragma unroll
+        for (int q = 0; q < 2; ++q)
+            bk_fft[(row * 4 + (size_t)o) * kHalf + 256 * q + threadIdx.x] = x[2 * o + q];
 }
 
 // ------------------------------------------------------------------------------------------
-// Blind rotation of B gates per workgroup, 256 threads (4 waves) per gate.
+// Blind rotation, one gate per workgroup of 256 threads (4 waves).
 //   prologue  c = (0, kappa) + m (s0 c0 + s1 c1); abar_j = round(c_j * 2N / 2^32); ACC = (0, X^-bbar v)
-//   n steps   D = X^abar_i ACC - ACC; 4 digit polynomials -> 4 forward FFTs (wave r);
-//             products with the transform-domain key row (all threads, one key load shared by the
-//             B gates); 4 inverse FFTs (wave o = component, limb); ACC += rounded results
+//   n steps   D = X^abar_i ACC - ACC; wave r = (component, digit) decomposes its digit polynomial
+//             and runs pass 1 of its forward FFT; after a barrier wave w carries the frequencies
+//             k0 = 2w, 2w+1 of all four polynomials through passes 2 and 3, gathers the four
+//             spectra of each of its frequencies into one lane, multiplies them with the key row
+//             in registers, scatters the four output spectra o = (component, limb) back and runs
+//             the inverse passes 3 and 2; after a second barrier wave o runs inverse pass 1,
+//             rounds and adds into ACC; a third barrier closes the step
 //   epilogue  sample extraction of coefficient 0 -> ext[gate][1025]
+// A workgroup takes gates blockIdx.x, blockIdx.x + gridDim.x, ...; launches normally have one
+// workgroup per gate (see resident_groups()).
 // ------------------------------------------------------------------------------------------
 struct GateLds {
-    double2 spec[4][kBufWords];   // per wave: FFT scratch, then spectrum / product in slot order
     uint32_t acc[2][kN];          // accumulator (mask, body), stored bitwise complemented: ~ACC = -ACC - 1
+    double2 buf[kBufWords];       // the four polynomials' transform buffers
     uint16_t bar[1032];           // abar_0 .. abar_{n-1}, bbar
 };
-// the rotation or-s a masked offset into the accumulator's address when that is 4 KB aligned
-static_assert(offsetof(GateLds, acc) % (kN * sizeof(uint32_t)) == 0, "accumulator at a multiple of 4 KB");
+// The rotation or-s a masked offset into the accumulator's LDS address: each component must start
+// at a multiple of 4 KB.  The kernels declare no other LDS, so the dynamic block starts at 0.
+static_assert(offsetof(GateLds, acc) == 0 && sizeof(uint32_t) * kN == 4096, "accumulator components 4 KB aligned");
 
 __device__ __forceinline__ void gate_constants(int op, uint32_t &kappa, uint32_t &mult) {
     switch (op) {
@@ -151,46 +138,59 @@ __device__ __forceinline__ double2 load_key(__amdgpu_buffer_rsrc_t rsrc, uint32_
     return out;
 }
 
-// AHEAD: how many of the step's key-load parts (a part = 8 values = 32 registers; a step of a
-// one-gate workgroup has 4) are loaded for step i + 1 as soon as the products of step i are
-// done, so that their latency hides behind the inverse transforms, the rotation and the
-// forward transforms.  All of them only for launches that leave one workgroup per CU; at full
-// occupancy other workgroups already cover that latency (one part ahead: no measurable gain).
-// TPG: threads per gate, 256 or 512.  The transforms, the rotation and the accumulation are the
-// work of four waves; with 512 threads the other four waves only take their share of the
-// spectral products (one slot per thread instead of two), which shortens a lone gate's step.
-template <int B, bool MARGIN, int AHEAD, int TPG = kThreadsPerGate>
+// A step's key values of one thread come in four parts of 8 (32 registers): part p = 2 q + h holds
+// rows r = 0..3 x outputs o = 2h, 2h+1 at the thread's slot 256 q + tid.
+// AHEAD: the latency variant (launches that leave one workgroup per CU) requests the whole key
+// row of step i + 1 while step i still runs, in eight portions of four loads placed between the
+// phases that follow the products of step i: a portion keeps the CU's one address unit busy for
+// 4 x 16 clocks per wave, and a wave alone on its SIMD cannot issue anything else meanwhile, so
+// portions issued back to back stall all four waves (measured on 64 gates: all 32 loads in one
+// place 2.06 ms, two places 1.82 ms, four 1.71 ms, eight 1.62 ms; no key traffic at all 1.50 ms).
+// At full occupancy other workgroups cover the loads and holding registers for them does not pay.
+template <bool MARGIN, int AHEAD>
 __device__ __forceinline__ void blind_rotate_body(const BlindRotateArgs &a) {
     extern __shared__ __align__(16) unsigned char lds_raw[];
-    GateLds *lds = reinterpret_cast<GateLds *>(lds_raw);
+    GateLds &my = *reinterpret_cast<GateLds *>(lds_raw);
+    static_assert(AHEAD == 0 || AHEAD == 4, "no key values or a whole step's ahead");
 
     const int tid = threadIdx.x;
-    static_assert(TPG == 256 || TPG == 512, "four or eight waves per gate");
-    const int g = tid / TPG;               // gate slot in this workgroup
-    const int lt = tid % TPG;              // thread within the gate
-    const int wv = lt >> 6;                // wave within the gate
-    const bool fft_wave = TPG == 256 || wv < 4;    // wave-uniform
+    const int wv = tid >> 6;               // wave
     const int L = tid & 63;
-    GateLds &my = lds[g];
-    const size_t gi = (size_t)blockIdx.x * B + g;
-    const bool live = gi < a.count;
 
     Lane ln;
     lane_init(ln, a.tables, L);
     const __amdgpu_buffer_rsrc_t key_rsrc = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<double2 *>(a.bk_fft), 0, (int)((size_t)a.n * 16 * kHalf * sizeof(double2)), 0x00020000);
+    const uint32_t voff = (uint32_t)tid * (uint32_t)sizeof(double2);
+    auto key_offset = [](int row, int part, int r, int o2) {
+        return (uint32_t)row * 16u * kHalf * (uint32_t)sizeof(double2) +
+               (uint32_t)(((r * 4 + 2 * (part & 1) + o2) * kHalf + 256 * (part >> 1)) * sizeof(double2));
+    };
 
+    const int comp = wv >> 1;                   // pass 1 forward: component of D; inverse: component of ACC
+    const int sel = wv & 1;                     // pass 1 forward: digit index; inverse: limb
+    // Signed digit `sel` of x: add the rounding constant and the half-bases of the lower digits
+    // (not its own: its two's-complement field then already is the centred digit), move the
+    // field to the top of the word, shift back down arithmetically.
+    const uint32_t dround = 1u << (31 - 2 * a.bgbit);
+    const uint32_t doffset = sel ? dround : dround + (1u << (31 - a.bgbit));
+    const uint32_t dfield = (uint32_t)(32 - a.bgbit * (1 + sel));   // lowest bit of the digit's field
+    double2 *const poly = my.buf + wv * kPolyStride;      // pass 1: this wave's polynomial
+    double2 *const mine = my.buf + row_of(wv, L);         // passes 2, 3: this lane's row
+    double worst = 0.0;
+
+    for (size_t gi = blockIdx.x; gi < a.count; gi += gridDim.x) {
     // ---- prologue ----
     {
         int op = a.uniform_op;
         size_t i0 = gi, i1 = gi;
         uint32_t s0 = 1u, s1 = 1u;
         const uint32_t *src1 = a.in1;
-        if (live && a.recs) {
+        if (a.recs) {
             const tfhe_gate_rec r = a.recs[gi];
             op = r.op; i0 = (size_t)r.in0; i1 = (size_t)r.in1;
             s0 = r.neg0 ? 0xFFFFFFFFu : 1u; s1 = r.neg1 ? 0xFFFFFFFFu : 1u;
-        } else if (live && op == TFHE_MUX) {
+        } else if (op == TFHE_MUX) {
             i0 = i1 = gi >> 1;
             if (gi & 1) { op = TFHE_MUX_ELSE; src1 = a.in1_alt; }
         }
@@ -201,12 +201,9 @@ __device__ __forceinline__ void blind_rotate_body(const BlindRotateArgs &a) {
         uint32_t kappa, mult;
         gate_constants(op, kappa, mult);
         const size_t w = (size_t)a.n + 1;
-        for (int j = lt; j <= a.n; j += TPG) {
-            uint32_t c = 0;
-            if (live) {
-                c = mult * (s0 * a.in0[i0 * w + j] + s1 * src1[i1 * w + j]);
-                if (j == a.n) c += kappa;
-            }
+        for (int j = tid; j <= a.n; j += kThreadsPerGate) {
+            uint32_t c = mult * (s0 * a.in0[i0 * w + j] + s1 * src1[i1 * w + j]);
+            if (j == a.n) c += kappa;
             my.bar[j] = (uint16_t)(((c + (1u << 20)) >> 21) & 2047u);
         }
     }
@@ -215,50 +212,34 @@ __device__ __forceinline__ void blind_rotate_body(const BlindRotateArgs &a) {
         const int bbar = my.bar[a.n];
         const int bb = bbar & (kN - 1);
         const uint32_t first = bbar < kN ? kEighth : 0u - kEighth;   // X^-bbar v, closed form
-        for (int j = lt; j < kN; j += TPG) {
+        for (int j = tid; j < kN; j += kThreadsPerGate) {
             my.acc[0][j] = ~0u;
             my.acc[1][j] = ~(j < kN - bb ? first : 0u - first);
         }
     }
     __syncthreads();
 
-    const int comp = (wv & 3) >> 1;             // forward: component of D; inverse: component of ACC
-    const int sel = wv & 1;                     // forward: digit index; inverse: limb
-    // Signed digit `sel` of x: add the rounding constant and the half-bases of the lower digits
-    // (not its own: its two's-complement field then already is the centred digit), move the
-    // field to the top of the word, shift back down arithmetically.
-    const uint32_t dround = 1u << (31 - 2 * a.bgbit);
-    const uint32_t doffset = sel ? dround : dround + (1u << (31 - a.bgbit));
-    const uint32_t dfield = (uint32_t)(32 - a.bgbit * (1 + sel));   // lowest bit of the digit's field
-    double worst = 0.0;
-
-    constexpr int kSlotsPerThread = (kHalf + TPG * B - 1) / (TPG * B);
-    static_assert(AHEAD >= 0 && AHEAD <= 2 * kSlotsPerThread, "parts of one step");
-    double2 ahead[AHEAD ? AHEAD : 1][4][2];     // [part = 2 * pass + half][row][output]
-    auto load_ahead = [&](int row) {
-        const uint32_t row_bytes = (uint32_t)row * 16u * kHalf * (uint32_t)sizeof(double2);
+    double2 ahead[AHEAD ? AHEAD : 1][4][2];     // [part][row][output of the pair]
+    // portion e of 8: rows 2 (e & 1), 2 (e & 1) + 1 of part e >> 1
+    auto load_ahead = [&](int row, int e) {
+        if (!AHEAD) return;
 #pragma unroll
-        for (int part = 0; part < AHEAD; ++part)
+        for (int r = 2 * (e & 1); r < 2 * (e & 1) + 2; ++r)
 #pragma unroll
-            for (int r = 0; r < 4; ++r)
-#pragma unroll
-                for (int o = 0; o < 2; ++o)
-                    ahead[part][r][o] = load_key(
-                        key_rsrc, (uint32_t)(tid + (part >> 1) * TPG * B) * (uint32_t)sizeof(double2),
-                        row_bytes + (uint32_t)((r * 4 + 2 * (part & 1) + o) * kHalf * sizeof(double2)));
+            for (int o2 = 0; o2 < 2; ++o2)
+                ahead[e >> 1][r][o2] = load_key(key_rsrc, voff, key_offset(row, e >> 1, r, o2));
     };
-    if (AHEAD) load_ahead(0);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) load_ahead(0, e);
 
     int abar_next = my.bar[0];
     for (int i = 0; i < a.n; ++i) {
         double2 x[8];
-        if (fft_wave) {
+        {
         // ---- rotate, subtract, decompose, fold and twist ----
         // read one step ahead (off the critical path); the same in every lane, so it goes to a scalar
         // register and the per-coefficient offsets below are scalar arithmetic
         const int abar = __builtin_amdgcn_readfirstlane(abar_next);
-        // LDS address of the component's accumulator as an integer: 4 KB aligned when the workgroup holds
-        // one gate (dynamic LDS starts at 0), so that a masked offset can be or-ed in
         typedef __attribute__((address_space(3))) const uint32_t lds_word;
         const uint32_t acc_at = (uint32_t)(uintptr_t)(lds_word *)my.acc[comp];
         const uint32_t lane4 = (uint32_t)L << 2;
@@ -275,19 +256,11 @@ __device__ __forceinline__ void blind_rotate_body(const BlindRotateArgs &a) {
             }
         // all sixteen rotated reads are issued before any of them is consumed
         uint32_t rot[8][2];
-        if ((acc_at & 4095u) == 0) {              // wave-uniform; true for one gate per workgroup
 #pragma unroll
-            for (int m = 0; m < 8; ++m)
+        for (int m = 0; m < 8; ++m)
 #pragma unroll
-                for (int h = 0; h < 2; ++h)
-                    rot[m][h] = *(lds_word *)(uintptr_t)and_or(lane4 + shift4[m][h], 4092u, acc_at);
-        } else {
-#pragma unroll
-            for (int m = 0; m < 8; ++m)
-#pragma unroll
-                for (int h = 0; h < 2; ++h)
-                    rot[m][h] = *(lds_word *)(uintptr_t)(((lane4 + shift4[m][h]) & 4092u) + acc_at);
-        }
+            for (int h = 0; h < 2; ++h)
+                rot[m][h] = *(lds_word *)(uintptr_t)and_or(lane4 + shift4[m][h], 4092u, acc_at);
 #pragma unroll
         for (int m = 0; m < 8; ++m) {
             int32_t dig[2];
@@ -305,67 +278,67 @@ __device__ __forceinline__ void blind_rotate_body(const BlindRotateArgs &a) {
             }
             x[m] = make_double2((double)dig[0], (double)dig[1]);
         }
-        forward_to_slots(x, ln, my.spec[wv & 3], L);
         }
+        if (i > 0) load_ahead(i, 6);
+        fwd_pass1_store(x, ln, poly, L);
         __syncthreads();
-        // The short phase between the two barriers starts with the key loads: waves in it go first
-        // (measured: 3 % faster than equal priorities; raising it in other phases loses).
-        __builtin_amdgcn_s_setprio(2);
+        if (i > 0) load_ahead(i, 7);
 
-        // ---- products with the key row: thread <-> slot, all gates of the workgroup ----
-        {
-            // key row i through a buffer descriptor: scalar base and row offset, 32-bit lane offset
-            const uint32_t row_bytes = (uint32_t)i * 16u * kHalf * (uint32_t)sizeof(double2);
+        // ---- this wave's frequencies of all four polynomials ----
+        fwd_pass2_load(x, mine, L);
+        wave_sync();
+        fwd_pass2_store(x, ln, mine, L);
+        wave_sync();
+        fwd_pass3(x, mine, L);
+        gather_rows(x);                      // x[2 r + q]: digit polynomial r at slot 256 q + tid
+
+        // ---- products with the key row, in registers: y[2 o + q] = sum_r x[2 r + q] key[r][o] ----
+        double2 y[8];
 #pragma unroll
-            for (int pass = 0; pass < kSlotsPerThread; ++pass) {
-                const int s = tid + pass * TPG * B;
-                if (TPG * B * kSlotsPerThread != kHalf && s >= kHalf) break;
-                const uint32_t voff = (uint32_t)s * (uint32_t)sizeof(double2);   // uniform base + 32-bit offset
-                double2 d[B][4];
+        for (int part = 0; part < 4; ++part) {
+            const int q = part >> 1;
+            double2 k[4][2];
 #pragma unroll
-                for (int q = 0; q < B; ++q)
+            for (int r = 0; r < 4; ++r)
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) d[q][r] = lds[q].spec[r][s];
-                // two outputs at a time keeps the key values of one pass in 32 registers
+                for (int o2 = 0; o2 < 2; ++o2)
+                    k[r][o2] = part < AHEAD ? ahead[part < AHEAD ? part : 0][r][o2]
+                                            : load_key(key_rsrc, voff, key_offset(i, part, r, o2));
 #pragma unroll
-                for (int half = 0; half < 2; ++half) {
-                    double2 k[4][2];
+            for (int o2 = 0; o2 < 2; ++o2) {
+                // fused multiply-adds, two independent chains per output
+                const double2 d0 = x[q];
+                double yr = d0.x * k[0][o2].x, yi = d0.x * k[0][o2].y;
+                double zr = -d0.y * k[0][o2].y, zi = d0.y * k[0][o2].x;
 #pragma unroll
-                    for (int r = 0; r < 4; ++r)
-#pragma unroll
-                        for (int o = 0; o < 2; ++o)
-                            k[r][o] = 2 * pass + half < AHEAD
-                                          ? ahead[2 * pass + half < AHEAD ? 2 * pass + half : 0][r][o]
-                                          : load_key(key_rsrc, voff, row_bytes + (uint32_t)((r * 4 + 2 * half + o) *
-                                                                                                 kHalf * sizeof(double2)));
-#pragma unroll
-                    for (int q = 0; q < B; ++q)
-#pragma unroll
-                        for (int o = 0; o < 2; ++o) {
-                            // fused multiply-adds, two independent chains per part
-                            double yr = d[q][0].x * k[0][o].x, yi = d[q][0].x * k[0][o].y;
-                            double zr = -d[q][0].y * k[0][o].y, zi = d[q][0].y * k[0][o].x;
-#pragma unroll
-                            for (int r = 1; r < 4; ++r) {
-                                yr = fma(d[q][r].x, k[r][o].x, yr);
-                                yi = fma(d[q][r].x, k[r][o].y, yi);
-                                zr = fma(-d[q][r].y, k[r][o].y, zr);
-                                zi = fma(d[q][r].y, k[r][o].x, zi);
-                            }
-                            yr += zr; yi += zi;
-                            lds[q].spec[2 * half + o][s] = make_double2(yr, yi);
-                        }
+                for (int r = 1; r < 4; ++r) {
+                    const double2 d = x[2 * r + q];
+                    yr = fma(d.x, k[r][o2].x, yr);
+                    yi = fma(d.x, k[r][o2].y, yi);
+                    zr = fma(-d.y, k[r][o2].y, zr);
+                    zi = fma(d.y, k[r][o2].x, zi);
                 }
+                y[2 * (2 * (part & 1) + o2) + q] = make_double2(yr + zr, yi + zi);
             }
         }
-        __syncthreads();
-        __builtin_amdgcn_s_setprio(0);
-        if (AHEAD) load_ahead(i + 1 < a.n ? i + 1 : i);
-        abar_next = my.bar[i + 1];           // bar[n] exists (it holds bbar)
+        const int next = i + 1 < a.n ? i + 1 : i;     // the last step requests its own row again
+        load_ahead(next, 0);
 
-        // ---- inverse transform, exact rounding, accumulate ----
-        if (fft_wave) {
-        inverse_from_slots(x, ln, my.spec[wv & 3], L);
+        // ---- back: scatter the four output spectra to their lanes, inverse passes 3 and 2 ----
+        scatter_rows(y);
+        inv_pass3_store(y, ln, mine, L);
+        wave_sync();
+        load_ahead(next, 1);
+        inv_pass2(y, mine, L);
+        wave_sync();
+        load_ahead(next, 2);
+        inv_pass2_store(y, mine, L);
+        __syncthreads();
+        abar_next = my.bar[i + 1];           // bar[n] exists (it holds bbar)
+        load_ahead(next, 3);
+
+        // ---- inverse pass 1 of output polynomial o = wave, exact rounding, accumulate ----
+        inv_pass1(x, ln, poly, L);
 #pragma unroll
         for (int m = 0; m < 8; ++m) {
             const double part[2] = {x[m].x, x[m].y};
@@ -377,19 +350,22 @@ __device__ __forceinline__ void blind_rotate_body(const BlindRotateArgs &a) {
                 uint32_t r = (uint32_t)__double2loint(shifted);
                 if (MARGIN) worst = fmax(worst, fabs(part[h] + (shifted - 6755399441055744.0)));
                 if (sel) r <<= 16;
+                if (m == 3 && h == 1) load_ahead(next, 4);
                 atomicAdd(&my.acc[comp][L + 64 * m + h * kHalf], r);
             }
         }
-        }
         __syncthreads();
+        load_ahead(next, 5);
     }
 
     // ---- epilogue: the constant coefficient as an LWE sample under the ring key ----
-    if (live) {
+    {
         uint32_t *ext = a.ext + gi * (size_t)(kN + 1);
         // ACC = ~c, -ACC = c + 1
-        for (int j = lt; j < kN; j += TPG) ext[j] = j == 0 ? ~my.acc[0][0] : my.acc[0][kN - j] + 1u;
-        if (lt == 0) ext[kN] = ~my.acc[1][0];
+        for (int j = tid; j < kN; j += kThreadsPerGate) ext[j] = j == 0 ? ~my.acc[0][0] : my.acc[0][kN - j] + 1u;
+        if (tid == 0) ext[kN] = ~my.acc[1][0];
+    }
+    __syncthreads();          // the next gate's prologue overwrites the accumulator
     }
     if (MARGIN) {
         // non-negative doubles order like their bit patterns
@@ -398,16 +374,16 @@ __device__ __forceinline__ void blind_rotate_body(const BlindRotateArgs &a) {
     }
 }
 
-template <int B, bool MARGIN>
-__global__ __launch_bounds__(kThreadsPerGate *B) __attribute__((amdgpu_waves_per_eu(3, 3))) void blind_rotate_kernel(BlindRotateArgs a) {
-    blind_rotate_body<B, MARGIN, 0>(a);
+template <bool MARGIN>
+__global__ __launch_bounds__(kThreadsPerGate) __attribute__((amdgpu_waves_per_eu(3, 3))) void blind_rotate_kernel(BlindRotateArgs a) {
+    blind_rotate_body<MARGIN, 0>(a);
 }
 
-// The same step for batches of at most one gate per CU, where a gate's latency is all that counts.
-constexpr int kLatencyThreads = 512;
+// The same step for batches of at most one gate per CU, where a gate's latency is all that
+// counts: the whole key row of step i + 1 is requested while step i still runs.
 template <bool MARGIN>
-__global__ __launch_bounds__(kLatencyThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void blind_rotate_latency_kernel(BlindRotateArgs a) {
-    blind_rotate_body<1, MARGIN, 2, kLatencyThreads>(a);
+__global__ __launch_bounds__(kThreadsPerGate) __attribute__((amdgpu_waves_per_eu(1, 1))) void blind_rotate_latency_kernel(BlindRotateArgs a) {
+    blind_rotate_body<MARGIN, 4>(a);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -483,93 +459,6 @@ __global__ void zero_outputs_kernel(KeySwitchArgs a) {
     const size_t out_index = a.recs ? (size_t)a.recs[gi].out : (a.uniform_mux ? gi >> 1 : gi);
     uint32_t *out = a.out + out_index * (size_t)(a.n + 1);
     for (int w = threadIdx.x; w <= a.n; w += blockDim.x) out[w] = 0u;
-}
-
-// ------------------------------------------------------------------------------------------
-// Key switch, G gates per workgroup (the fast path for t = 8 digits in base 4, n + 1 <= 512).
-// Every key row is loaded once per workgroup and subtracted from the gates whose digit selects
-// it, so the key traffic per gate is 1/G of the one-gate-per-workgroup kernel.  Thread p owns the
-// adjacent output words 2p, 2p+1 of all G gates.  For one (mask word i, digit position j) each
-// wave parks its 128-word slice of the three rows in a private LDS table whose row 0 stays
-// zero; a gate's digit is uniform over the workgroup, so the gate picks its row with a uniform
-// LDS offset -- the LDS does the gather.  The rounded mask words of the G gates are staged
-// through LDS 64 at a time.
-// ------------------------------------------------------------------------------------------
-template <int G>
-__global__ __launch_bounds__(256) void key_switch_shared_kernel(KeySwitchArgs a) {
-    constexpr int T = 8, kChunk = 64;
-    __shared__ uint32_t mask_words[kChunk][G];
-    __shared__ uint2 stage[4][4][64];             // [wave][digit value][lane]
-    const int tid = threadIdx.x;
-    const int wave = tid >> 6, lane = tid & 63;
-    const size_t g0 = (size_t)blockIdx.x * G;
-    const int words = a.n + 1;
-    const bool owner = 2 * tid < words;            // 2p+1 may be the zero padding word of a row
-    const int pair = owner ? tid : 0;              // idle threads shadow pair 0 and store nothing
-
-    // an item is live if it exists and is not the second half of a multiplexer
-    auto is_live = [&](size_t gi) {
-        if (gi >= a.count) return false;
-        return a.recs ? a.recs[gi].op != TFHE_MUX_ELSE : !(a.uniform_mux && (gi & 1));
-    };
-    uint2 acc[G];
-#pragma unroll
-    for (int g = 0; g < G; ++g) {
-        const bool live = is_live(g0 + g);
-        const uint32_t body = live ? a.ext[(g0 + g) * (size_t)(kN + 1) + kN] : 0u;
-        acc[g].x = 2 * pair == a.n ? body : 0u;
-        acc[g].y = 2 * pair + 1 == a.n ? body : 0u;
-    }
-    stage[wave][0][lane] = make_uint2(0u, 0u);
-    const uint32_t round = 1u << (31 - T * 2);
-    const unsigned char *table = reinterpret_cast<const unsigned char *>(&stage[wave][0][lane]);
-    for (int i0 = 0; i0 < kN; i0 += kChunk) {
-        __syncthreads();
-        for (int idx = tid; idx < kChunk * G; idx += 256) {
-            const int g = idx / kChunk, ii = idx % kChunk;
-            const bool live = is_live(g0 + g);
-            mask_words[ii][g] = live ? a.ext[(g0 + g) * (size_t)(kN + 1) + i0 + ii] + round : 0u;
-        }
-        __syncthreads();
-        for (int ii = 0; ii < kChunk; ++ii) {
-            const uint32_t *rows = a.ksk + (size_t)(i0 + ii) * T * 3 * a.stride;
-            uint2 r[T][3];
-#pragma unroll
-            for (int j = 0; j < T; ++j)
-#pragma unroll
-                for (int v = 0; v < 3; ++v)
-                    r[j][v] = *reinterpret_cast<const uint2 *>(rows + (size_t)(j * 3 + v) * a.stride + 2 * pair);
-            uint32_t ai[G];
-#pragma unroll
-            for (int g = 0; g < G; ++g) ai[g] = __builtin_amdgcn_readfirstlane(mask_words[ii][g]);
-#pragma unroll
-            for (int j = 0; j < T; ++j) {
-                wave_sync();                       // the previous table has been read by every lane
-#pragma unroll
-                for (int v = 0; v < 3; ++v) stage[wave][v + 1][lane] = r[j][v];
-                wave_sync();
-#pragma unroll
-                for (int g = 0; g < G; ++g) {
-                    const uint32_t v = (ai[g] >> (30 - 2 * j)) & 3u;
-                    const uint2 sub = *reinterpret_cast<const uint2 *>(table + v * (64 * sizeof(uint2)));
-                    acc[g].x -= sub.x;
-                    acc[g].y -= sub.y;
-                }
-            }
-        }
-    }
-    if (owner) {
-#pragma unroll
-        for (int g = 0; g < G; ++g) {
-            if (is_live(g0 + g)) {
-                const size_t out_index =
-                    a.recs ? (size_t)a.recs[g0 + g].out : (a.uniform_mux ? (g0 + g) >> 1 : g0 + g);
-                uint32_t *out = a.out + out_index * (size_t)words;
-                out[2 * pair] = acc[g].x;
-                if (2 * pair + 1 < words) out[2 * pair + 1] = acc[g].y;
-            }
-        }
-    }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -761,19 +650,60 @@ __global__ void fill_trivial_kernel(uint32_t *ct, int words, uint32_t body) {
     for (int w = threadIdx.x; w < words; w += blockDim.x) ct[w] = w == words - 1 ? body : 0u;
 }
 
+// Register-resident double-precision FMA loop: what the vector ALU of this device sustains when
+// nothing but arithmetic is in the way (16 independent chains per lane, no memory traffic).  The
+// blind rotation's achieved rate is quoted against this measured figure beside the published peak.
+constexpr int kPeakChains = 16, kPeakUnroll = 8;
+__global__ __launch_bounds__(256) void fp64_fma_peak_kernel(double *sink, int iters, double a, double b) {
+    double v[kPeakChains];
+#pragma unroll
+    for (int c = 0; c < kPeakChains; ++c) v[c] = (double)(threadIdx.x + c) * 1e-9;
+    for (int i = 0; i < iters; ++i)
+#pragma unroll
+        for (int u = 0; u < kPeakUnroll; ++u)
+#pragma unroll
+            for (int c = 0; c < kPeakChains; ++c) v[c] = fma(v[c], a, b);
+    double total = 0.0;
+#pragma unroll
+    for (int c = 0; c < kPeakChains; ++c) total += v[c];
+    if (total == 12345.678) sink[0] = total;       // never true: keeps the chains alive
+}
+
 }  // namespace
+
+// Compute units of the current device (cached).
+static int device_cus() {
+    static const int cus = [] {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess)
+            return n;
+        return 0;
+    }();
+    return cus;
+}
 
 // Largest batch that goes to the latency variant: one gate per compute unit of the device.
 static int latency_batch_limit() {
     static const int limit = [] {
         if (const char *e = getenv("TFHE_LATENCY_BATCH")) return atoi(e);
-        int dev = 0, cus = 0;
-        if (hipGetDevice(&dev) == hipSuccess &&
-            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess)
-            return cus;
-        return 0;
+        return device_cus();
     }();
     return limit;
+}
+
+// Upper bound on the workgroups of a throughput launch, 0 = none (one workgroup per gate, the
+// default).  With a bound -- three per CU is what stays resident -- each workgroup takes every
+// grid-th gate and all of them walk the key rows together from the first gate to the last.
+// Measured on 12,288 gates: workgroups that start together stay in the same phase of the step,
+// so their transform, product and key-load phases coincide instead of overlapping, and the
+// launch takes 68 ms against 56 ms with one workgroup per gate, whose start times spread out.
+static int resident_groups() {
+    static const int groups = [] {
+        if (const char *e = getenv("TFHE_RESIDENT_GROUPS")) { const int v = atoi(e); if (v > 0) return v; }
+        return 0;
+    }();
+    return groups;
 }
 
 // Kernels that use more than 64 KB of dynamic LDS have to be told so once per device;
@@ -788,7 +718,7 @@ static int allow_dynamic_lds(const void *kernel, size_t bytes, std::atomic<uint6
     return TFHE_OK;
 }
 
-size_t blind_rotate_lds_bytes(int gates_per_group) { return sizeof(GateLds) * (size_t)gates_per_group; }
+size_t blind_rotate_lds_bytes() { return sizeof(GateLds); }
 
 // ------------------------------------------------------------------------------------------
 // Scratch of the entry point that allocates nothing: the extracted samples between the blind
@@ -823,67 +753,55 @@ uint32_t *static_scratch_ptr() {
 
 int launch_bk_to_spectrum(const uint32_t *bk_raw, double2 *bk_fft, const double2 *tables, int n,
                           hipStream_t stream) {
-    const unsigned blocks = (unsigned)n * 4 * 2 * 2;
-    hipLaunchKernelGGL(bk_to_spectrum_kernel, dim3(blocks), dim3(64), 0, stream, bk_raw, bk_fft, tables);
+    hipLaunchKernelGGL(bk_to_spectrum_kernel, dim3((unsigned)n * 4), dim3(256), 0, stream, bk_raw, bk_fft, tables);
     TFHE_HIP(hipGetLastError());
     return TFHE_OK;
 }
 
-template <int B>
-static int launch_br(const BlindRotateArgs &a, hipStream_t stream) {
-    const size_t lds = blind_rotate_lds_bytes(B);
-    static std::atomic<uint64_t> plain{0}, with_margin{0};
-    if (int rc = allow_dynamic_lds(reinterpret_cast<const void *>(&blind_rotate_kernel<B, false>), lds, plain)) return rc;
-    if (int rc = allow_dynamic_lds(reinterpret_cast<const void *>(&blind_rotate_kernel<B, true>), lds, with_margin)) return rc;
-    const unsigned blocks = (unsigned)((a.count + B - 1) / B);
-    if (a.margin)
-        hipLaunchKernelGGL((blind_rotate_kernel<B, true>), dim3(blocks), dim3(kThreadsPerGate * B), lds, stream, a);
-    else
-        hipLaunchKernelGGL((blind_rotate_kernel<B, false>), dim3(blocks), dim3(kThreadsPerGate * B), lds, stream, a);
-    TFHE_HIP(hipGetLastError());
-    return TFHE_OK;
-}
-
-// Batches that leave at most one gate per CU: the variant that loads each key row a step ahead.
-static int launch_br_latency(const BlindRotateArgs &a, hipStream_t stream) {
-    const size_t lds = blind_rotate_lds_bytes(1);
-    static std::atomic<uint64_t> plain{0}, with_margin{0};
-    if (int rc = allow_dynamic_lds(reinterpret_cast<const void *>(&blind_rotate_latency_kernel<false>), lds, plain)) return rc;
-    if (int rc = allow_dynamic_lds(reinterpret_cast<const void *>(&blind_rotate_latency_kernel<true>), lds, with_margin)) return rc;
-    if (a.margin)
-        hipLaunchKernelGGL(blind_rotate_latency_kernel<true>, dim3((unsigned)a.count), dim3(kLatencyThreads), lds, stream, a);
-    else
-        hipLaunchKernelGGL(blind_rotate_latency_kernel<false>, dim3((unsigned)a.count), dim3(kLatencyThreads), lds, stream, a);
-    TFHE_HIP(hipGetLastError());
-    return TFHE_OK;
-}
-
-int launch_blind_rotate(const BlindRotateArgs &a, int gates_per_group, hipStream_t stream) {
-    if (a.count == 0) return TFHE_OK;
-    if (gates_per_group == 1 && a.count <= (size_t)latency_batch_limit()) return launch_br_latency(a, stream);
-    switch (gates_per_group) {
-    case 1: return launch_br<1>(a, stream);
-    case 2: return launch_br<2>(a, stream);
-    case 3: return launch_br<3>(a, stream);
-    default: return set_error(TFHE_E_PARAM, "unsupported gates per workgroup %d", gates_per_group);
-    }
-}
+// the four blind-rotation kernels and the two matrix-core key-switch kernels, with their
+// dynamic LDS sizes and per-device "attribute set" masks
+namespace {
+struct BigLdsKernel { const void *fn; size_t lds; std::atomic<uint64_t> done; };
+BigLdsKernel big_lds_kernels[6] = {
+    {reinterpret_cast<const void *>(&blind_rotate_kernel<false>), sizeof(GateLds), {0}},
+    {reinterpret_cast<const void *>(&blind_rotate_kernel<true>), sizeof(GateLds), {0}},
+    {reinterpret_cast<const void *>(&blind_rotate_latency_kernel<false>), sizeof(GateLds), {0}},
+    {reinterpret_cast<const void *>(&blind_rotate_latency_kernel<true>), sizeof(GateLds), {0}},
+    {reinterpret_cast<const void *>(&key_switch_mfma_kernel<false>), sizeof(KsMatrixLds), {0}},
+    {reinterpret_cast<const void *>(&key_switch_mfma_kernel<true>), sizeof(KsMatrixLds), {0}},
+};
+int allow(int which) { return allow_dynamic_lds(big_lds_kernels[which].fn, big_lds_kernels[which].lds, big_lds_kernels[which].done); }
+}  // namespace
 
 // Everything a launch would otherwise set up on first use (dynamic-LDS permissions, the cached
-// device properties), done once per device at key upload so that later calls only launch.
+// device properties, the address of the static scratch), done once per device at key upload so
+// that later calls only launch.
 int prepare_kernels() {
     (void)latency_batch_limit();
-    const size_t lds = blind_rotate_lds_bytes(1);
-    static std::atomic<uint64_t> unused[6];
-    const void *kernels[6] = {reinterpret_cast<const void *>(&blind_rotate_kernel<1, false>),
-                              reinterpret_cast<const void *>(&blind_rotate_kernel<1, true>),
-                              reinterpret_cast<const void *>(&blind_rotate_latency_kernel<false>),
-                              reinterpret_cast<const void *>(&blind_rotate_latency_kernel<true>),
-                              reinterpret_cast<const void *>(&key_switch_mfma_kernel<false>),
-                              reinterpret_cast<const void *>(&key_switch_mfma_kernel<true>)};
+    (void)resident_groups();
     for (int k = 0; k < 6; ++k)
-        if (int rc = allow_dynamic_lds(kernels[k], k < 4 ? lds : sizeof(KsMatrixLds), unused[k])) return rc;
+        if (int rc = allow(k)) return rc;
     return static_scratch_init();
+}
+
+int launch_blind_rotate(const BlindRotateArgs &a, hipStream_t stream) {
+    if (a.count == 0) return TFHE_OK;
+    const size_t lds = sizeof(GateLds);
+    const bool latency = a.count <= (size_t)latency_batch_limit();
+    if (int rc = allow((latency ? 2 : 0) + (a.margin ? 1 : 0))) return rc;
+    if (latency) {
+        // at most one gate per CU: the variant that requests each key row a step ahead
+        const dim3 grid((unsigned)a.count);
+        if (a.margin) hipLaunchKernelGGL(blind_rotate_latency_kernel<true>, grid, dim3(kThreadsPerGate), lds, stream, a);
+        else hipLaunchKernelGGL(blind_rotate_latency_kernel<false>, grid, dim3(kThreadsPerGate), lds, stream, a);
+    } else {
+        const size_t bound = (size_t)resident_groups();
+        const dim3 grid((unsigned)(bound ? std::min(a.count, bound) : a.count));
+        if (a.margin) hipLaunchKernelGGL(blind_rotate_kernel<true>, grid, dim3(kThreadsPerGate), lds, stream, a);
+        else hipLaunchKernelGGL(blind_rotate_kernel<false>, grid, dim3(kThreadsPerGate), lds, stream, a);
+    }
+    TFHE_HIP(hipGetLastError());
+    return TFHE_OK;
 }
 
 int launch_ksk_to_tiles(const uint32_t *ksk, int stride, int words, void *tiles, hipStream_t stream) {
@@ -898,16 +816,12 @@ size_t ksk_tiles_bytes() { return (size_t)16 * kN * 4 * 64 * sizeof(v4i); }
 int launch_key_switch(const KeySwitchArgs &a, hipStream_t stream) {
     if (a.count == 0) return TFHE_OK;
     if (a.ksk_tiles && a.matrix && a.t == 8 && a.basebit == 2 && a.n + 1 <= 512) {
-        static std::atomic<uint64_t> whole{0}, split{0};
-        if (int rc = allow_dynamic_lds(reinterpret_cast<const void *>(&key_switch_mfma_kernel<false>), sizeof(KsMatrixLds), whole))
-            return rc;
-        if (int rc = allow_dynamic_lds(reinterpret_cast<const void *>(&key_switch_mfma_kernel<true>), sizeof(KsMatrixLds), split))
-            return rc;
         // fewer than one workgroup per CU: share each gate's mask words between workgroups
         KeySwitchArgs m = a;
         const unsigned row_blocks = (unsigned)((a.count + kKsRows - 1) / kKsRows);
         m.splits = 1;
         while (m.splits < 32 && row_blocks * 8 * m.splits < 256) m.splits *= 2;
+        if (int rc = allow(m.splits > 1 ? 5 : 4)) return rc;
         if (m.splits > 1) {
             hipLaunchKernelGGL(zero_outputs_kernel, dim3((unsigned)a.count), dim3(256), 0, stream, m);
             TFHE_HIP(hipGetLastError());
@@ -917,18 +831,6 @@ int launch_key_switch(const KeySwitchArgs &a, hipStream_t stream) {
             hipLaunchKernelGGL(key_switch_mfma_kernel<true>, grid, dim3(256), sizeof(KsMatrixLds), stream, m);
         else
             hipLaunchKernelGGL(key_switch_mfma_kernel<false>, grid, dim3(256), sizeof(KsMatrixLds), stream, m);
-        TFHE_HIP(hipGetLastError());
-        return TFHE_OK;
-    }
-    if (a.t == 8 && a.basebit == 2 && a.n + 1 <= 512 && a.group > 1) {
-        // more gates per workgroup = less key traffic per gate but fewer, longer workgroups
-#define KS_SHARED(G)                                                                                   \
-    hipLaunchKernelGGL(key_switch_shared_kernel<G>, dim3((unsigned)((a.count + G - 1) / G)), dim3(256), 0, \
-                       stream, a)
-        if (a.group >= 16) KS_SHARED(16);
-        else if (a.group >= 8) KS_SHARED(8);
-        else KS_SHARED(4);
-#undef KS_SHARED
         TFHE_HIP(hipGetLastError());
         return TFHE_OK;
     }
@@ -963,6 +865,34 @@ int launch_gather_outputs(const uint32_t *wires, const tfhe_out_ref *refs, uint3
     hipLaunchKernelGGL(gather_outputs_kernel, dim3((unsigned)count), dim3(256), 0, stream, wires, refs, out,
                        count, words);
     TFHE_HIP(hipGetLastError());
+    return TFHE_OK;
+}
+
+// Time the FMA loop with HIP events on `stream`; *tflops = achieved double-precision rate.
+int measure_fp64_fma_peak(hipStream_t stream, double *sink, double *tflops) {
+    const int cus = device_cus() > 0 ? device_cus() : 256;
+    const int blocks = cus * 8, iters = 4096;               // 8 workgroups of 4 waves per CU: 8 waves per SIMD
+    hipEvent_t t0, t1;
+    TFHE_HIP(hipEventCreate(&t0));
+    TFHE_HIP(hipEventCreate(&t1));
+    float best = 0.0f;
+    int rc = TFHE_OK;
+    for (int rep = 0; rep < 3 && rc == TFHE_OK; ++rep) {      // the first launch warms the clocks up
+        hipError_t e = hipEventRecord(t0, stream);
+        hipLaunchKernelGGL(fp64_fma_peak_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, sink, iters, 0.999999, 1e-7);
+        if (e == hipSuccess) e = hipGetLastError();
+        if (e == hipSuccess) e = hipEventRecord(t1, stream);
+        if (e == hipSuccess) e = hipEventSynchronize(t1);
+        float ms = 0.0f;
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, t0, t1);
+        if (e != hipSuccess) { rc = set_error(TFHE_E_HIP, "FMA peak measurement failed: %s", hipGetErrorString(e)); break; }
+        if (rep == 0 || ms < best) best = ms;
+    }
+    (void)hipEventDestroy(t0);
+    (void)hipEventDestroy(t1);
+    if (rc) return rc;
+    const double flops = 2.0 * kPeakChains * kPeakUnroll * (double)iters * 256.0 * (double)blocks;
+    *tflops = flops / ((double)best * 1e-3) / 1e12;
     return TFHE_OK;
 }
 

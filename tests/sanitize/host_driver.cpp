@@ -14,7 +14,7 @@ namespace tfhe {
 static int unreachable(const char *what) { std::fprintf(stderr, "device launcher %s reached\n", what); std::abort(); }
 size_t blind_rotate_lds_bytes(int) { return 0; }
 int launch_bk_to_spectrum(const uint32_t *, double2 *, const double2 *, int, hipStream_t) { return unreachable("bk"); }
-int launch_blind_rotate(const BlindRotateArgs &, int, hipStream_t) { return unreachable("blind_rotate"); }
+int launch_blind_rotate(const BlindRotateArgs &, hipStream_t) { return unreachable("blind_rotate"); }
 int launch_key_switch(const KeySwitchArgs &, hipStream_t) { return unreachable("key_switch"); }
 size_t ksk_tiles_bytes() { return 0; }
 int launch_ksk_to_tiles(const uint32_t *, int, int, void *, hipStream_t) { return unreachable("tiles"); }
@@ -22,6 +22,7 @@ int launch_mux_combine(uint32_t *, const tfhe_gate_rec *, size_t, hipStream_t) {
 int launch_gather_outputs(const uint32_t *, const tfhe_out_ref *, uint32_t *, size_t, int, hipStream_t) { return unreachable("gather"); }
 int launch_fill_trivial(uint32_t *, int, int, hipStream_t) { return unreachable("fill"); }
 int prepare_kernels() { return unreachable("prepare"); }
+int measure_fp64_fma_peak(hipStream_t, double *, double *) { return unreachable("peak"); }
 uint32_t *static_scratch_ptr() { return nullptr; }
 size_t static_scratch_gates() { return 4096; }
 }  // namespace tfhe
@@ -73,6 +74,17 @@ int main() {
             tfhe_gate_rec *g = nullptr; tfhe_out_ref *o = nullptr; size_t ng = 0, no = 0, nw = 0;
             CHECK(bnn_dense_lower_opts(d, W.data(), T.data(), p, 0, f, &g, &ng, &o, &no, &nw) == TFHE_OK);
             CHECK(no == (size_t)p && nw >= (size_t)d + 2);
+            {   // the wire-pool schedule of the layer calls on the same circuit
+                tfhe_gate_rec *planned = nullptr; size_t pool = 0, depths = 0;
+                CHECK(tfhe_plan_wire_pool(g, ng, nw, (size_t)d + 2, o, no, &planned, &pool, &depths) == TFHE_OK);
+                CHECK(pool >= (size_t)d + 2 && pool <= nw && depths >= 1);
+                for (size_t k = 0; k < ng; ++k)
+                    CHECK((size_t)planned[k].in0 < pool && (size_t)planned[k].in1 < pool && (size_t)planned[k].out < pool);
+                tfhe_free_buffer(planned);
+                tfhe_gate_rec cyclic = g[0];
+                cyclic.in0 = cyclic.out;
+                CHECK(tfhe_plan_wire_pool(&cyclic, 1, nw, (size_t)d + 2, nullptr, 0, &planned, &pool, &depths) == TFHE_E_PARAM);
+            }
             tfhe_free_buffer(g); tfhe_free_buffer(o);
             if (f & TFHE_LOWER_MUX_COMPARATOR) continue;
             std::vector<int8_t> K(3 * 2 * 3 * 3);

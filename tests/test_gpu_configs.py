@@ -82,8 +82,15 @@ def test_cfg3_dense_layer(gpu, golden, real_keys):
     # (2) all 512 outputs against the integer layer
     assert np.array_equal(T.tfhe_decrypt(sk, out), cc.dense_plain(c["x"], c["W"], c["T"]))
     # (1) whole neurons computed from scratch by the oracle
-    for j in (0, 257):
+    for j in (0, 257, 100, 511):
         assert digest(out[j]) == golden[("cfg3", (j,))]["sha256"], j
+    # the layer entry point (wire pool with recycled slots) gives the same 512 ciphertexts
+    res = torch.empty((512, 501), dtype=torch.int32, device="cuda")
+    T.bnn_dense_encrypted(ck, T.to_device(ctx), 784, c["W"], c["T"], 512, res)
+    torch.cuda.synchronize()
+    assert np.array_equal(T.to_host(res), out)
+    st = T.tfhe_last_layer_stats(ck)
+    assert st["gates"] == len(gates) and st["depths"] == 36 and st["pool_wires"] < 0.45 * nw
     # (3) 256 random gates anywhere in the circuit, oracle on the GPU's input wires
     rng = np.random.default_rng(33)
     pick = np.sort(rng.choice(len(gates), 256, replace=False))
@@ -97,26 +104,66 @@ def test_cfg3_dense_layer(gpu, golden, real_keys):
     assert np.array_equal(work[2 * k:], take(sel["out"]))
 
 
-def test_cfg4_conv_layer(gpu, golden, capsys):
+CFG4_PIXELS = [(0, 0, 0), (5, 0, 13), (17, 13, 27), (31, 27, 27), (9, 14, 14), (20, 27, 3),
+               (1, 0, 27), (2, 27, 0), (3, 13, 0), (4, 27, 14), (6, 0, 1), (7, 1, 0), (8, 26, 27), (10, 27, 26),
+               (11, 1, 1), (12, 26, 26), (13, 7, 19), (14, 19, 7), (15, 12, 15), (16, 3, 24), (18, 24, 3),
+               (19, 10, 10), (21, 17, 22), (22, 22, 17), (23, 5, 5), (24, 15, 12), (25, 8, 21), (26, 21, 8),
+               (27, 13, 13), (28, 2, 16), (29, 16, 2), (30, 25, 11)]
+
+
+def test_cfg4_conv_layer(gpu, golden, real_keys, capsys):
     import torch
     T, sk, ck = gpu
+
+    def say(msg):
+        with capsys.disabled():
+            sys.stderr.write(f"[cfg4] {msg}\n")
+            sys.stderr.flush()
+
     c = workloads.cfg4()
     x = T.to_device(T.tfhe_encrypt(sk, c["enc_seed"], c["x"].reshape(-1)))
     out = torch.empty((32 * 28 * 28, 501), dtype=torch.int32, device="cuda")
-    # four calls of 8 output channels each (units are independent, so the circuits are the same
-    # as in one call); a progress line after each keeps a watching pipe alive
-    for part in range(4):
-        ch = slice(8 * part, 8 * part + 8)
-        T.bnn_conv_encrypted(ck, x, 16, 28, 28, c["K"][ch], c["T"][ch], 1, 1, out[8 * part * 784:(8 * part + 8) * 784])
-        torch.cuda.synchronize()
-        with capsys.disabled():
-            sys.stderr.write(f"[cfg4] output channels {8 * part}..{8 * part + 7} done\n")
-            sys.stderr.flush()
+    # the whole layer as one call: 25,088 units, 24.4 M gates
+    T.bnn_conv_encrypted(ck, x, 16, 28, 28, c["K"], c["T"], 1, 1, out)
+    torch.cuda.synchronize()
+    st = T.tfhe_last_layer_stats(ck)
+    say(f"one call done: {st['gates']} gates, {st['depths']} depths, wire pool {st['pool_wires']} of "
+        f"{st['circuit_wires']} wires ({st['pool_wires'] * 2004 / 1e9:.1f} GB)")
+    assert st["gates"] > 24_000_000 and st["pool_wires"] < 0.45 * st["circuit_wires"]
     got = T.to_host(out)
+    # (2) every output pixel against the integer layer
     plain = cc.conv_plain(c["x"], c["K"], c["T"], 1, 1)
     assert np.array_equal(T.tfhe_decrypt(sk, got).reshape(32, 28, 28), plain)
-    for (o, y, xx) in [(0, 0, 0), (5, 0, 13), (17, 13, 27), (31, 27, 27), (9, 14, 14), (20, 27, 3)]:
+    # (1) 32 pixels computed from scratch by the oracle: corners, edges, interior, every channel
+    for (o, y, xx) in CFG4_PIXELS:
         assert digest(got[(o * 28 + y) * 28 + xx]) == golden[("cfg4", (o, y, xx))]["sha256"], (o, y, xx)
+    # (3) eight output channels again as a gate stream on wires the test owns (no slot reuse): the
+    # same output bytes, and 256 random gates anywhere in it re-evaluated by the oracle on the GPU's wires
+    ch = slice(8, 16)
+    gates, outs, nw = T.bnn_conv_lower(16, 28, 28, c["K"][ch], c["T"][ch], 1, 1)
+    wires = torch.zeros((nw, 501), dtype=torch.int32, device="cuda")
+    nin = 16 * 28 * 28
+    wires[:nin] = x
+    wires[nin] = T.to_device(T.tfhe_trivial(T.default_params(), 0).reshape(1, -1))[0]
+    wires[nin + 1] = T.to_device(T.tfhe_trivial(T.default_params(), 1).reshape(1, -1))[0]
+    T.tfhe_gate_stream(ck, gates, wires, nw)
+    torch.cuda.synchronize()
+    say(f"gate stream of channels 8..15 done ({len(gates)} gates)")
+    take = lambda w: T.to_host(wires[torch.from_numpy(w.astype(np.int64)).cuda()])
+    assert (outs["wire"] >= nin + 2).all()
+    slice_out = take(outs["wire"])
+    neg = outs["value"].astype(bool)
+    slice_out[neg] = (0 - slice_out[neg]).astype(np.uint32)
+    assert np.array_equal(slice_out, got[8 * 784:16 * 784])
+    rng = np.random.default_rng(44)
+    pick = np.sort(rng.choice(len(gates), 256, replace=False))
+    sel = gates[pick]
+    k = len(sel)
+    work = np.concatenate([take(sel["in0"]), take(sel["in1"]), np.zeros((k, 501), np.uint32)])
+    recs = sel.copy()
+    recs["in0"], recs["in1"], recs["out"] = np.arange(k), k + np.arange(k), 2 * k + np.arange(k)
+    real_keys.gate_batch(recs, work, threads=16)
+    assert np.array_equal(work[2 * k:], take(sel["out"]))
 
 
 def test_cfg5_sparse_mlp(gpu, golden, real_keys):
@@ -143,8 +190,8 @@ def test_cfg5_sparse_mlp(gpu, golden, real_keys):
     # (1) first-layer neurons from scratch
     for j in (0, 100):
         assert digest(host[1][j]) == golden[("cfg5", (0, j))]["sha256"], j
-    # (3) one whole neuron of each later layer, oracle fed with the GPU's activations
-    for li, j in ((1, 7), (2, 3)):
+    # (3) two whole units of each later layer, oracle fed with the GPU's activations
+    for li, j in ((1, 7), (1, 200), (2, 3), (2, 9)):
         layer = c["layers"][li]
         last = layer["T"] is None
         cir, outs = cc.dense_layer(layer["W"].shape[1], layer["W"][j:j + 1],

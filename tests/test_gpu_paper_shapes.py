@@ -133,3 +133,29 @@ def test_faces_shape_one_channel(gpu, golden, real_keys):
     cir, outs = cc.dense_layer(25, D["W"], None, ob)
     ref, _ = cc.eval_encrypted(real_keys, cir, host[5], outs, threads=16)
     assert np.array_equal(final, ref)
+
+
+def test_faces_shape_first_convolution_at_32_channels(gpu, golden):
+    """The first convolution of the Faces shape at the paper's width (Sec. 5.2: 32 output channels,
+    10 x 10 windows on the 50 x 50 image): 53,792 units, 36 M gates, as one call.  Every output pixel
+    is decrypted against the integer layer; six pixels are compared with digests the oracle computed
+    from scratch.  (The later convolutions at this width read 3,200 inputs per unit, 732 M gates
+    each, about fifty minutes of GPU time per layer: they run at reduced width in the test above.)"""
+    import torch
+    T, sk, ck = gpu
+    c = workloads.paper_faces(channels=32)
+    L = c["convs"][0]
+    x = T.to_device(T.tfhe_encrypt(sk, c["enc_seed"], c["x"].reshape(-1)))
+    plain = cc.conv_plain(c["x"], L["K"], L["T"], 1, 0)
+    assert plain.shape == (32, 41, 41)
+    out = torch.empty((plain.size, 501), dtype=torch.int32, device="cuda")
+    say("[faces32] first convolution: (1, 50, 50) -> (32, 41, 41)")
+    T.bnn_conv_encrypted(ck, x, 1, 50, 50, L["K"], L["T"], 1, 0, out)
+    torch.cuda.synchronize()
+    st = T.tfhe_last_layer_stats(ck)
+    say(f"[faces32] {st['gates']} gates, {st['depths']} depths, wire pool {st['pool_wires']} of {st['circuit_wires']} wires")
+    assert st["gates"] > 30_000_000
+    got = T.to_host(out)
+    assert np.array_equal(T.tfhe_decrypt(sk, got).reshape(plain.shape), plain)
+    for (o, y, xx) in ((0, 0, 0), (13, 40, 40), (31, 17, 23), (7, 0, 40), (22, 40, 0), (18, 20, 20)):
+        assert digest(got[(o * 41 + y) * 41 + xx]) == golden[("faces32", (0, o, y, xx))]["sha256"], (o, y, xx)

@@ -361,6 +361,26 @@ def test_launch_chunking_does_not_change_results(gpu):
     assert digests[0] == digests[1]
 
 
+def test_throughput_kernel_with_a_bounded_grid_gives_the_same_bytes(gpu):
+    """The same calls in a process that sends every launch to the throughput kernel with at most 5
+    workgroups (each workgroup then walks several gates, the last ones fewer than the first) give the
+    bytes of the default process, where launches this small go to the latency kernel with one
+    workgroup per gate."""
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    digests = []
+    for knobs in ({}, {"TFHE_LATENCY_BATCH": "0", "TFHE_RESIDENT_GROUPS": "5"}, {"TFHE_LATENCY_BATCH": "0"}):
+        env = dict(os.environ)
+        for k in ("TFHE_LATENCY_BATCH", "TFHE_RESIDENT_GROUPS", "TFHE_CHUNK_GATES"):
+            env.pop(k, None)
+        env.update(knobs)
+        r = subprocess.run([sys.executable, "-c", _CHUNK_SCRIPT, root], env=env, stdout=subprocess.PIPE,
+                           stderr=subprocess.STDOUT, text=True, timeout=300)
+        assert r.returncode == 0, r.stdout
+        digests.append([l for l in r.stdout.splitlines() if l.startswith("digest")][-1])
+    assert digests[0] == digests[1] == digests[2]
+
+
 @pytest.mark.parametrize("pattern", ["all_min", "alternating", "random"])
 def test_extreme_key_limbs_stay_exact(gpu, orc, pattern):
     """Exactness of the split-integer FP64 products does not depend on the key being 'typical':

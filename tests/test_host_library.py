@@ -18,7 +18,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "tfhe_mi355x.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
-    declared = set(re.findall(r"\b((?:tfhe|bnn)_[a-z_]+)\s*\(", header))
+    declared = set(re.findall(r"\b((?:tfhe|bnn)_[a-z0-9_]+)\s*\(", header))
     assert {"tfhe_keygen", "tfhe_encrypt", "tfhe_decrypt", "tfhe_gate_batch", "tfhe_gate_stream",
             "bnn_dense_encrypted", "bnn_conv_encrypted"} <= declared
     L = T.lib()
@@ -317,3 +317,104 @@ def test_argument_errors_are_reported_not_thrown():
     ln = C.c_size_t(3)
     buf = (C.c_uint32 * 1)()
     assert L.tfhe_export_key(sk2.handle, T.KEY_LWE_SK, buf, C.byref(ln)) == -3 and ln.value == 32
+
+
+def _plain_gate(op, a, b):
+    return {T.NAND: 1 - (a & b), T.AND: a & b, T.OR: a | b, T.NOR: 1 - (a | b), T.XOR: a ^ b, T.XNOR: 1 - (a ^ b)}[op]
+
+
+def _eval_circuit_bits(gates, nwires, fixed_bits):
+    """Plain evaluation of gate records on bits, one wire per index (the definition)."""
+    w = np.zeros(nwires, np.int64)
+    w[:len(fixed_bits)] = fixed_bits
+    g = 0
+    while g < len(gates):
+        r = gates[g]
+        a, b = w[r["in0"]] ^ r["neg0"], w[r["in1"]] ^ r["neg1"]
+        if r["op"] == T.MUX:
+            e = gates[g + 1]
+            w[r["out"]] = b if a else (w[e["in1"]] ^ e["neg1"])
+            g += 2
+        else:
+            w[r["out"]] = _plain_gate(int(r["op"]), int(a), int(b))
+            g += 1
+    return w
+
+
+def _asap_levels(gates, nwires):
+    depth = np.zeros(nwires, np.int64)
+    lv = np.zeros(len(gates), np.int64)
+    for g, r in enumerate(gates):
+        if r["op"] == T.MUX_ELSE:
+            lv[g] = lv[g - 1]
+            continue
+        l = 1 + max(depth[r["in0"]], depth[r["in1"]])
+        if r["op"] == T.MUX:
+            l = max(l, 1 + depth[gates[g + 1]["in1"]])
+        lv[g] = l
+        depth[r["out"]] = l
+    return lv
+
+
+@pytest.mark.parametrize("flags", [T.LOWER_DEFAULT, T.LOWER_MUX_COMPARATOR, T.LOWER_PLUS_ONE | T.LOWER_SHARE_GATES,
+                                   T.LOWER_SORTING_NETWORK])
+def test_wire_pool_plan_keeps_the_circuit_and_never_reuses_a_live_slot(flags):
+    """tfhe_plan_wire_pool (the schedule of the layer calls): run depth by depth -- all reads of a
+    depth before its writes, as the two kernels of a launch do -- the renamed records give the
+    outputs of the circuit as lowered; no slot written at a depth is read at that depth; fixed
+    wires and outputs keep their slots; the pool is smaller than one slot per wire."""
+    rng = np.random.default_rng(int(flags) + 3)
+    d, p = 23, 9
+    W = rng.choice(np.array([-1, 0, 1], np.int8), (p, d), p=[0.47, 0.06, 0.47])
+    W[0] = 0
+    W[0, 5] = -1                                    # a unit that is one negated input: no gate
+    Tt = rng.integers(4, 15, p).astype(np.int32)
+    Tt[0], Tt[1] = 1, 0                             # unit 0: that input's negation; unit 1: constant 1
+    gates, outs, nw = T.bnn_dense_lower_opts(d, W, Tt, p, 0, flags)
+    planned, pouts, pool, depths = T.tfhe_plan_wire_pool(gates, nw, d + 2, outs)
+    lv = _asap_levels(gates, nw)
+    assert depths == lv.max() and len(planned) == len(gates)
+    assert d + 2 < pool < nw and pool <= d + 2 + (gates["op"] != T.MUX_ELSE).sum()
+    counts = np.bincount(lv, minlength=depths + 1)
+    bounds = np.concatenate([[0], np.cumsum(counts[1:])])
+    # the plan is the stable depth sort of the records: same opcodes and flags in that order
+    order = np.argsort(lv, kind="stable")
+    for f in ("op", "neg0", "neg1"):
+        assert np.array_equal(planned[f], gates[f][order])
+    for trial in range(8):
+        x = rng.integers(0, 2, d)
+        fixed = np.concatenate([x, [0, 1]])
+        want_w = _eval_circuit_bits(gates, nw, fixed)
+        want = [(want_w[o["wire"]] ^ o["value"]) if o["wire"] >= 0 else o["value"] for o in outs]
+        slots = np.full(pool, -7, np.int64)
+        slots[:d + 2] = fixed
+        for l in range(1, depths + 1):
+            recs = planned[bounds[l - 1]:bounds[l]]
+            reads = set(recs["in0"]) | set(recs["in1"])
+            writes = set(recs["out"][recs["op"] != T.MUX_ELSE])
+            assert not (reads & writes), l                      # a launch reads its inputs before it writes
+            assert min(writes) >= d + 2
+            a = slots[recs["in0"]] ^ recs["neg0"]
+            b = slots[recs["in1"]] ^ recs["neg1"]
+            assert (a >= 0).all() and (b >= 0).all() and (a <= 1).all() and (b <= 1).all()
+            res = {}
+            for k, r in enumerate(recs):
+                if r["op"] == T.MUX:
+                    res[int(r["out"])] = int(b[k]) if a[k] else int(b[k + 1])
+                elif r["op"] != T.MUX_ELSE:
+                    res[int(r["out"])] = _plain_gate(int(r["op"]), int(a[k]), int(b[k]))
+            for s, v in res.items():
+                slots[s] = v
+        got = [(slots[o["wire"]] ^ o["value"]) if o["wire"] >= 0 else o["value"] for o in pouts]
+        assert got == want
+    # pass-through and constant outputs keep their meaning
+    if flags == T.LOWER_DEFAULT:
+        assert pouts[0]["wire"] == 5 and pouts[0]["value"] == 1 and pouts[1]["wire"] == -1 and pouts[1]["value"] == 1
+
+
+def test_wire_pool_of_the_benchmark_layer_is_a_fraction_of_its_wires():
+    c3 = workloads.cfg3()
+    gates, outs, nw = T.bnn_dense_lower(784, c3["W"][:64], c3["T"][:64], 64)
+    planned, pouts, pool, depths = T.tfhe_plan_wire_pool(gates, nw, 786, outs)
+    assert depths == 36 and pool < 0.45 * nw
+    assert len(set(pouts["wire"])) == 64 and pouts["wire"].min() >= 786      # outputs keep distinct slots
