@@ -361,24 +361,26 @@ def test_launch_chunking_does_not_change_results(gpu):
     assert digests[0] == digests[1]
 
 
-def test_throughput_kernel_with_a_bounded_grid_gives_the_same_bytes(gpu):
-    """The same calls in a process that sends every launch to the throughput kernel with at most 5
-    workgroups (each workgroup then walks several gates, the last ones fewer than the first) give the
-    bytes of the default process, where launches this small go to the latency kernel with one
-    workgroup per gate."""
+def test_kernel_choices_do_not_change_results(gpu):
+    """The same calls give the same bytes whichever kernels serve them: the default process (launches
+    this small: latency variant of the blind rotation, matrix-core key switch with split mask words);
+    every launch sent to the throughput kernel, with one workgroup per gate and with at most 5
+    workgroups (each then walks several gates, the last ones fewer than the first); the gather key
+    switch at the benchmark parameters, with a gate's mask words split over workgroups and not."""
     import subprocess
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
     digests = []
-    for knobs in ({}, {"TFHE_LATENCY_BATCH": "0", "TFHE_RESIDENT_GROUPS": "5"}, {"TFHE_LATENCY_BATCH": "0"}):
+    for knobs in ({}, {"TFHE_LATENCY_BATCH": "0", "TFHE_RESIDENT_GROUPS": "5"}, {"TFHE_LATENCY_BATCH": "0"},
+                  {"TFHE_KS_MATRIX_FROM": "0"}, {"TFHE_KS_MATRIX_FROM": "0", "TFHE_KS_SPLITS": "1"}):
         env = dict(os.environ)
-        for k in ("TFHE_LATENCY_BATCH", "TFHE_RESIDENT_GROUPS", "TFHE_CHUNK_GATES"):
+        for k in ("TFHE_LATENCY_BATCH", "TFHE_RESIDENT_GROUPS", "TFHE_CHUNK_GATES", "TFHE_KS_MATRIX_FROM", "TFHE_KS_SPLITS"):
             env.pop(k, None)
         env.update(knobs)
         r = subprocess.run([sys.executable, "-c", _CHUNK_SCRIPT, root], env=env, stdout=subprocess.PIPE,
                            stderr=subprocess.STDOUT, text=True, timeout=300)
         assert r.returncode == 0, r.stdout
         digests.append([l for l in r.stdout.splitlines() if l.startswith("digest")][-1])
-    assert digests[0] == digests[1] == digests[2]
+    assert len(set(digests)) == 1, digests
 
 
 @pytest.mark.parametrize("pattern", ["all_min", "alternating", "random"])
