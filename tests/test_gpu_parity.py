@@ -361,6 +361,14 @@ def test_launch_chunking_does_not_change_results(gpu):
     assert digests[0] == digests[1]
 
 
+def test_measured_fp64_ceiling_is_plausible(gpu):
+    """The register-resident FMA loop that bench.py quotes the blind rotation against reaches a rate
+    between half of and the whole published vector FP64 peak of the device."""
+    T, _, ck = gpu
+    tflops = T.tfhe_measure_fp64_peak(ck)
+    assert 35.0 < tflops < 82.0, tflops
+
+
 def test_kernel_choices_do_not_change_results(gpu):
     """The same calls give the same bytes whichever kernels serve them: the default process (launches
     this small: latency variant of the blind rotation, matrix-core key switch with split mask words);

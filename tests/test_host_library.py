@@ -418,3 +418,35 @@ def test_wire_pool_of_the_benchmark_layer_is_a_fraction_of_its_wires():
     planned, pouts, pool, depths = T.tfhe_plan_wire_pool(gates, nw, 786, outs)
     assert depths == 36 and pool < 0.45 * nw
     assert len(set(pouts["wire"])) == 64 and pouts["wire"].min() >= 786      # outputs keep distinct slots
+
+
+def test_wire_pool_planner_rejects_malformed_circuits():
+    """The planner validates like the gate-stream executor: cycles, double writes, broken multiplexer
+    pairs, wires out of range, writes to fixed wires and outputs that nothing produces are errors."""
+    def rec(op, in0, in1, out, neg0=0, neg1=0):
+        return (op, neg0, neg1, 0, in0, in1, out)
+
+    def plan(recs, nwires=8, n_fixed=4, outs=((4, 0),)):
+        return T.tfhe_plan_wire_pool(np.array(recs, dtype=T.GATE_DTYPE), nwires, n_fixed,
+                                     np.array(list(outs), dtype=T.OUT_DTYPE))
+
+    planned, pouts, pool, depths = plan([rec(T.AND, 0, 1, 4), rec(T.OR, 4, 2, 5)], outs=((5, 1), (2, 0), (-1, 1)))
+    assert (pool, depths) == (6, 2) and list(pouts["wire"]) == [5, 2, -1] and list(pouts["value"]) == [1, 0, 1]
+    for bad, code in (([rec(T.AND, 0, 5, 4), rec(T.OR, 4, 2, 5)], -2),         # reads a wire written later
+                      ([rec(T.AND, 4, 1, 4)], -2),                              # reads its own output
+                      ([rec(T.AND, 0, 1, 4), rec(T.OR, 0, 2, 4)], -2),          # wire written twice
+                      ([rec(T.AND, 0, 1, 9)], -3),                              # wire out of range
+                      ([rec(T.AND, 0, 1, 2)], -2),                              # writes a fixed wire
+                      ([rec(T.MUX, 0, 1, 4)], -2),                              # multiplexer without its second record
+                      ([rec(T.MUX, 0, 1, 4), rec(T.MUX_ELSE, 3, 2, 4)], -2),    # other selector in the second record
+                      ([rec(T.MUX_ELSE, 0, 1, 4)], -2),
+                      ([rec(9, 0, 1, 4)], -2),                                  # unknown opcode
+                      ([rec(T.AND, 0, 6, 4)], -2)):                             # reads a wire nothing writes
+        with pytest.raises(T.TfheError) as e:
+            plan(bad)
+        assert e.value.code == code, (bad, str(e.value))
+    with pytest.raises(T.TfheError) as e:
+        plan([rec(T.AND, 0, 1, 4)], outs=((6, 0),))                            # output that nothing produces
+    assert e.value.code == -2
+    planned, pouts, pool, depths = plan([], outs=((1, 1),))                    # no gates at all
+    assert (len(planned), pool, depths) == (0, 4, 0)
