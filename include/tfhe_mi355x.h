@@ -34,7 +34,10 @@
  *     memory for the keys, up to 1.07 GB for the samples between the two kernels
  *     (4,100 B per gate of the widest launch) and, for the layer calls, a wire pool of
  *     one ciphertext (4 (n+1) bytes) per wire that is alive at the same time (about a
- *     third of the layer's gates; tfhe_last_layer_stats reports it).
+ *     third of the layer's gates; tfhe_last_layer_stats reports it).  A layer of more
+ *     than about 50 M gates whose units are lowered independently (every lowering but
+ *     the "+1" trick and gate sharing) is evaluated in groups of units, so its pool
+ *     stays below about 35 GB whatever its size.
  *   - The GPU path supports N = 1024, k = 1, bk_l = 2, bk_Bgbit <= 10, n <= 1024,
  *     ks_t * ks_basebit <= 24, ks_basebit <= 4; other parameters give TFHE_E_PARAM.
  */
@@ -285,7 +288,8 @@ int tfhe_plan_wire_pool(const tfhe_gate_rec *gates, size_t ngates, size_t nwires
  * wires of the lowered circuit (inputs, the two constants, one per gate), slots of the wire pool
  * it was evaluated in (a slot is reused once the last depth reading its wire has run; this is
  * the device memory the call needed, 4 (n+1) bytes per slot), and circuit depths (= kernel
- * pairs when no depth is wider than a launch). */
+ * pairs when no depth is wider than a launch).  For a layer evaluated in groups of units, gates
+ * and wires are totals, pool_wires and depths the largest of any group. */
 typedef struct {
     uint64_t gates, circuit_wires, pool_wires, depths;
 } tfhe_layer_stats;

@@ -462,8 +462,11 @@ int lower_dense(int d, const int8_t *W, const int32_t *T, int p, int out_bits, u
     return TFHE_OK;
 }
 
+// Units u0 <= u < u1 of the convolution in output order (u = (o * Ho + y) * Wo + x); a range other
+// than all units is only possible where units are lowered independently of each other.
 int lower_conv(int C, int H, int Wd, const int8_t *K, int O, int kh, int kw, int stride, int pad,
-               const int32_t *T, uint32_t flags, Builder &b, std::vector<tfhe_out_ref> &outs) {
+               const int32_t *T, uint32_t flags, Builder &b, std::vector<tfhe_out_ref> &outs,
+               long long u0 = 0, long long u1 = -1) {
     if (flags & ~(uint32_t)(TFHE_LOWER_PLUS_ONE | TFHE_LOWER_SHARE_GATES | TFHE_LOWER_SORTING_NETWORK))
         return set_error(TFHE_E_PARAM, "unknown lowering flags %u", flags);
     if ((flags & TFHE_LOWER_SORTING_NETWORK) && (flags & TFHE_LOWER_PLUS_ONE))
@@ -487,10 +490,12 @@ int lower_conv(int C, int H, int Wd, const int8_t *K, int O, int kh, int kw, int
     };
     if (!(flags & (TFHE_LOWER_PLUS_ONE | TFHE_LOWER_SHARE_GATES))) {
         if ((long long)O * Ho * Wo > INT32_MAX) return set_error(TFHE_E_SIZE, "too many output pixels");
-        return lower_units(O * Ho * Wo, taps, C * H * Wd, b, outs,
-                           [&](Builder &bb, std::vector<tfhe_out_ref> &oo, int u) {
+        if (u1 < 0) u1 = (long long)O * Ho * Wo;
+        return lower_units((int)(u1 - u0), taps, C * H * Wd, b, outs,
+                           [&](Builder &bb, std::vector<tfhe_out_ref> &oo, int k) {
                                thread_local std::vector<Sig> f;
                                f.resize(taps);
+                               const int u = (int)u0 + k;
                                const int o = u / (Ho * Wo), y = u / Wo % Ho, x = u % Wo;
                                gather_field(f, y, x, bb.zero_wire());
                                bb.unit(f, K + (size_t)o * taps, T + o, 0, oo, flags);
@@ -516,6 +521,34 @@ int lower_conv(int C, int H, int Wd, const int8_t *K, int O, int kh, int kw, int
             }
     return TFHE_OK;
 }
+
+// A layer whose units are lowered independently of each other is evaluated in groups of units
+// when its circuit is large: the host then never holds more than one group's records, and the
+// wire pool never more than one group's live wires, whatever the layer's size.  The bound is on
+// the estimated gates of a group; the function returns the units per group.
+long long units_per_group(long long units, size_t inputs_per_unit, uint32_t flags) {
+    if (flags & (TFHE_LOWER_PLUS_ONE | TFHE_LOWER_SHARE_GATES)) return units;     // units share gates
+    long long budget = 48ll << 20;                                                  // gates per group
+    if (const char *e = getenv("TFHE_LAYER_GROUP_GATES")) {                        // measurement and tests
+        const long long v = atoll(e);
+        if (v > 0) budget = v;
+    }
+    // gates per input: about 7 for the reduce tree, several times that for the sorting network
+    const long long per_unit = (long long)std::max<size_t>(1, inputs_per_unit) * ((flags & TFHE_LOWER_SORTING_NETWORK) ? 48 : 7);
+    return std::max<long long>(1, std::min(units, budget / per_unit));
+}
+
+// the statistics of a layer call cover all its groups: gates and wires add up, the pool is the largest
+struct LayerTotals {
+    size_t gates = 0, wires = 0, pool = 0, levels = 0;
+    void add(const tfhe_cloud_key *ck) {
+        gates += ck->last_layer_gates; wires += ck->last_layer_wires;
+        pool = std::max(pool, ck->last_layer_pool); levels = std::max(levels, ck->last_layer_levels);
+    }
+    void store(tfhe_cloud_key *ck) const {
+        ck->last_layer_gates = gates; ck->last_layer_wires = wires; ck->last_layer_pool = pool; ck->last_layer_levels = levels;
+    }
+};
 
 // wire pool = [inputs | noiseless 0 | noiseless 1 | recycled slots of the gate outputs]; run; gather the outputs
 int evaluate(tfhe_cloud_key *ck, Builder &b, std::vector<tfhe_out_ref> &outs, const uint32_t *x,
@@ -611,10 +644,21 @@ static int bnn_dense_encrypted_opts_impl(tfhe_cloud_key *ck, const uint32_t *x, 
     if (int rc = tfhe::ensure_uploaded(ck)) return rc;
     if (!x || !out) return set_error(TFHE_E_NULL, "NULL ciphertext buffer");
     if (d < 1) return set_error(TFHE_E_SIZE, "layer sizes must be positive");
-    Builder b(d, (flags & TFHE_LOWER_SHARE_GATES) != 0);
-    std::vector<tfhe_out_ref> o;
-    if (int rc = lower_dense(d, W, T, p, out_bits, flags, b, o)) return rc;
-    return evaluate(ck, b, o, x, d, out, (hipStream_t)stream);
+    if (p < 1) return set_error(TFHE_E_SIZE, "layer sizes must be positive");
+    if (!W) return set_error(TFHE_E_NULL, "W is NULL");
+    const long long group = units_per_group(p, (size_t)d, flags);
+    const size_t words = (size_t)ck->params.n + 1, outs_per_unit = T ? 1 : (size_t)std::max(out_bits, 0);
+    LayerTotals totals;
+    for (long long u0 = 0; u0 < p; u0 += group) {
+        const int count = (int)std::min<long long>(group, p - u0);
+        Builder b(d, (flags & TFHE_LOWER_SHARE_GATES) != 0);
+        std::vector<tfhe_out_ref> o;
+        if (int rc = lower_dense(d, W + (size_t)u0 * d, T ? T + u0 : nullptr, count, out_bits, flags, b, o)) return rc;
+        if (int rc = evaluate(ck, b, o, x, d, out + (size_t)u0 * outs_per_unit * words, (hipStream_t)stream)) return rc;
+        totals.add(ck);
+    }
+    totals.store(ck);
+    return TFHE_OK;
 }
 
 int bnn_dense_encrypted_opts(tfhe_cloud_key *ck, const uint32_t *x, int d, const int8_t *W, const int32_t *T,
@@ -634,10 +678,24 @@ static int bnn_conv_encrypted_opts_impl(tfhe_cloud_key *ck, const uint32_t *x, i
     if (!x || !out) return set_error(TFHE_E_NULL, "NULL ciphertext buffer");
     if (C < 1 || H < 1 || Wd < 1 || (long long)C * H * Wd > (1ll << 30))
         return set_error(TFHE_E_SIZE, "bad convolution shape");
-    Builder b(C * H * Wd, (flags & TFHE_LOWER_SHARE_GATES) != 0);
-    std::vector<tfhe_out_ref> o;
-    if (int rc = lower_conv(C, H, Wd, K, O, kh, kw, stride, pad, T, flags, b, o)) return rc;
-    return evaluate(ck, b, o, x, C * H * Wd, out, (hipStream_t)stream);
+    if (O < 1 || kh < 1 || kw < 1 || stride < 1 || pad < 0 || H + 2 * pad < kh || Wd + 2 * pad < kw)
+        return set_error(TFHE_E_SIZE, "bad convolution shape");
+    const long long Ho = (H + 2 * pad - kh) / stride + 1, Wo = (Wd + 2 * pad - kw) / stride + 1;
+    const long long units = (long long)O * Ho * Wo;
+    if (units > INT32_MAX) return set_error(TFHE_E_SIZE, "too many output pixels");
+    const long long group = units_per_group(units, (size_t)C * kh * kw, flags);
+    const size_t words = (size_t)ck->params.n + 1;
+    LayerTotals totals;
+    for (long long u0 = 0; u0 < units; u0 += group) {
+        const long long u1 = std::min(units, u0 + group);
+        Builder b(C * H * Wd, (flags & TFHE_LOWER_SHARE_GATES) != 0);
+        std::vector<tfhe_out_ref> o;
+        if (int rc = lower_conv(C, H, Wd, K, O, kh, kw, stride, pad, T, flags, b, o, u0, u1)) return rc;
+        if (int rc = evaluate(ck, b, o, x, C * H * Wd, out + (size_t)u0 * words, (hipStream_t)stream)) return rc;
+        totals.add(ck);
+    }
+    totals.store(ck);
+    return TFHE_OK;
 }
 
 int bnn_conv_encrypted_opts(tfhe_cloud_key *ck, const uint32_t *x, int C, int H, int Wd, const int8_t *K, int O,

@@ -329,6 +329,12 @@ for flags in (T.LOWER_MUX_COMPARATOR, T.LOWER_DEFAULT):
     T.bnn_dense_encrypted_opts(ck, ctx, d, W, Tt, p, res, 0, flags)
     torch.cuda.synchronize()
     h.update(T.to_host(res).tobytes())
+K = (2 * rng.integers(0, 2, (3, 2, 3, 3)) - 1).astype(np.int8)
+img = rng.integers(0, 2, 2 * 5 * 4).astype(np.uint8)
+res = torch.empty((3 * 5 * 4, 501), dtype=torch.int32, device="cuda")
+T.bnn_conv_encrypted(ck, T.to_device(T.tfhe_encrypt(sk, 94, img)), 2, 5, 4, K, np.array([8, 9, 10], np.int32), 1, 1, res)
+torch.cuda.synchronize()
+h.update(T.to_host(res).tobytes())
 s = rng.integers(0, 2, 13).astype(np.uint8)
 cs, ca, cb = (T.to_device(T.tfhe_encrypt(sk, 97 + k, s ^ k)) for k in range(3))
 out = torch.empty((13, 501), dtype=torch.int32, device="cuda")
@@ -374,14 +380,17 @@ def test_kernel_choices_do_not_change_results(gpu):
     this small: latency variant of the blind rotation, matrix-core key switch with split mask words);
     every launch sent to the throughput kernel, with one workgroup per gate and with at most 5
     workgroups (each then walks several gates, the last ones fewer than the first); the gather key
-    switch at the benchmark parameters, with a gate's mask words split over workgroups and not."""
+    switch at the benchmark parameters, with a gate's mask words split over workgroups and not; layer
+    calls that evaluate their units in groups of at most 300 estimated gates (two or three units)."""
     import subprocess
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
     digests = []
     for knobs in ({}, {"TFHE_LATENCY_BATCH": "0", "TFHE_RESIDENT_GROUPS": "5"}, {"TFHE_LATENCY_BATCH": "0"},
-                  {"TFHE_KS_MATRIX_FROM": "0"}, {"TFHE_KS_MATRIX_FROM": "0", "TFHE_KS_SPLITS": "1"}):
+                  {"TFHE_KS_MATRIX_FROM": "0"}, {"TFHE_KS_MATRIX_FROM": "0", "TFHE_KS_SPLITS": "1"},
+                  {"TFHE_LAYER_GROUP_GATES": "300"}):
         env = dict(os.environ)
-        for k in ("TFHE_LATENCY_BATCH", "TFHE_RESIDENT_GROUPS", "TFHE_CHUNK_GATES", "TFHE_KS_MATRIX_FROM", "TFHE_KS_SPLITS"):
+        for k in ("TFHE_LATENCY_BATCH", "TFHE_RESIDENT_GROUPS", "TFHE_CHUNK_GATES", "TFHE_KS_MATRIX_FROM", "TFHE_KS_SPLITS",
+                  "TFHE_LAYER_GROUP_GATES"):
             env.pop(k, None)
         env.update(knobs)
         r = subprocess.run([sys.executable, "-c", _CHUNK_SCRIPT, root], env=env, stdout=subprocess.PIPE,
