@@ -101,14 +101,16 @@ __global__ __launch_bounds__(256) void bk_to_spectrum_kernel(const uint32_t *__r
 // A workgroup takes gates blockIdx.x, blockIdx.x + gridDim.x, ...; launches normally have one
 // workgroup per gate (see resident_groups()).
 // ------------------------------------------------------------------------------------------
+constexpr int kMirror = 64;       // coefficients 0..63 of each accumulator component are kept a second time
 struct GateLds {
-    uint32_t acc[2][kN];          // accumulator (mask, body), stored bitwise complemented: ~ACC = -ACC - 1
+    // accumulator (mask, body), stored bitwise complemented: c = ~ACC = -ACC - 1.  Behind each component
+    // sits a mirror of its first 64 coefficients, stored as -c - 2: a rotated read of 64 consecutive
+    // coefficients that runs past X^N continues into the mirror, and the value found there already
+    // carries the sign change of X^N = -1 (see the rotation in blind_rotate_body)
+    uint32_t acc[2][kN + kMirror];
     double2 buf[kBufWords];       // the four polynomials' transform buffers
     uint16_t bar[1032];           // abar_0 .. abar_{n-1}, bbar
 };
-// The rotation or-s a masked offset into the accumulator's LDS address: each component must start
-// at a multiple of 4 KB.  The kernels declare no other LDS, so the dynamic block starts at 0.
-static_assert(offsetof(GateLds, acc) == 0 && sizeof(uint32_t) * kN == 4096, "accumulator components 4 KB aligned");
 
 __device__ __forceinline__ void gate_constants(int op, uint32_t &kappa, uint32_t &mult) {
     switch (op) {
@@ -119,13 +121,6 @@ __device__ __forceinline__ void gate_constants(int op, uint32_t &kappa, uint32_t
     case TFHE_XOR:  kappa = 2u * kEighth;     mult = 2u;          break;
     default:        kappa = 0u - 2u * kEighth; mult = 0xFFFFFFFEu; break;   // XNOR
     }
-}
-
-// (x & mask) | y in one instruction; mask is wave-uniform
-__device__ __forceinline__ uint32_t and_or(uint32_t x, uint32_t mask, uint32_t y) {
-    uint32_t r;
-    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(x), "s"(mask), "v"(y));
-    return r;
 }
 
 // 16-byte load from a buffer: descriptor and soffset are scalar, voffset is the lane's byte offset
@@ -154,7 +149,7 @@ __device__ __forceinline__ void blind_rotate_body(const BlindRotateArgs &a) {
     static_assert(AHEAD == 0 || AHEAD == 4, "no key values or a whole step's ahead");
 
     const int tid = threadIdx.x;
-    const int wv = tid >> 6;               // wave
+    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);     // wave, in a scalar register
     const int L = tid & 63;
 
     Lane ln;
@@ -223,8 +218,10 @@ __device__ __forceinline__ void blind_rotate_body(const BlindRotateArgs &a) {
         const int bb = bbar & (kN - 1);
         const uint32_t first = bbar < kN ? kEighth : 0u - kEighth;   // X^-bbar v, closed form
         for (int j = tid; j < kN; j += kThreadsPerGate) {
+            const uint32_t c = ~(j < kN - bb ? first : 0u - first);
             my.acc[0][j] = ~0u;
-            my.acc[1][j] = ~(j < kN - bb ? first : 0u - first);
+            my.acc[1][j] = c;
+            if (j < kMirror) { my.acc[0][kN + j] = 0u - ~0u - 2u; my.acc[1][kN + j] = 0u - c - 2u; }
         }
     }
     __syncthreads();
@@ -249,21 +246,33 @@ __device__ __forceinline__ void blind_rotate_body(const BlindRotateArgs &a) {
         {
         // ---- rotate, subtract, decompose, fold and twist ----
         // read one step ahead (off the critical path); the same in every lane, so it goes to a scalar
-        // register and the per-coefficient offsets below are scalar arithmetic
+        // register and everything below that does not depend on the lane is scalar arithmetic
         const int abar = __builtin_amdgcn_readfirstlane(abar_next);
         typedef __attribute__((address_space(3))) const uint32_t lds_word;
         const uint32_t acc_at = (uint32_t)(uintptr_t)(lds_word *)my.acc[comp];
         const uint32_t lane4 = (uint32_t)L << 2;
         const uint32_t back4 = (uint32_t)(0 - abar) << 2;       // X^abar reads abar coefficients back, mod 8192 bytes
-        // per coefficient: byte offset of its source = lane part + scalar part (kept on the scalar ALU)
-        uint32_t shift4[8][2];
+        // Coefficient j = L + 64 m + 512 h of X^abar ACC is +-ACC[(j - abar) mod N].  The 64 lanes read 64
+        // consecutive source coefficients starting at lane 0's, whose byte offset and sign are scalar.  The
+        // run wraps past X^N in exactly one of the sixteen (m, h), from some lane on; those lanes read
+        // on into the mirror behind the component, which holds mu = -c - 2 for the first 64 coefficients.
+        // With ACC stored as c = ~ACC, the step's  +-ACC[src] - ACC[j] + doffset  is
+        //   source not past X^N (flip = ~0):  -c[src] + c[j] + doffset = (c[src] ^ ~0) + c[j] + doffset + 1
+        //   source past X^N (flip = 0):        c[src] + c[j] + doffset + 2
+        // i.e. (c[src] ^ flip) + c[j] + (doffset + 2 + flip); a lane in the mirror needs the other flip,
+        // and (mu ^ flip) + flip = (c ^ ~flip) + ~flip for either flip: two vector instructions per
+        // coefficient, whatever the lane.
+        uint32_t from[8][2], flip[8][2], bias[8][2];
 #pragma unroll
         for (int m = 0; m < 8; ++m)
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
-                // + 4096: bit 12 of the sum then says "source not past X^N"
-                shift4[m][h] = back4 + (uint32_t)(64 * m + h * kHalf) * 4u + 4096u;
-                asm("" : "+s"(shift4[m][h]));
+                // + 4096: bit 12 of the sum then says "lane 0's source not past X^N"
+                const uint32_t s = back4 + (uint32_t)(64 * m + h * kHalf) * 4u + 4096u;
+                from[m][h] = acc_at + (s & 4095u);
+                flip[m][h] = (uint32_t)((int32_t)(s << 19) >> 31);
+                bias[m][h] = doffset + 2u + flip[m][h];
+                asm("" : "+s"(from[m][h]), "+s"(flip[m][h]), "+s"(bias[m][h]));
             }
         // all sixteen rotated reads are issued before any of them is consumed
         uint32_t rot[8][2];
@@ -271,20 +280,14 @@ __device__ __forceinline__ void blind_rotate_body(const BlindRotateArgs &a) {
         for (int m = 0; m < 8; ++m)
 #pragma unroll
             for (int h = 0; h < 2; ++h)
-                rot[m][h] = *(lds_word *)(uintptr_t)and_or(lane4 + shift4[m][h], 4092u, acc_at);
+                rot[m][h] = *(lds_word *)(uintptr_t)(lane4 + from[m][h]);
 #pragma unroll
         for (int m = 0; m < 8; ++m) {
             int32_t dig[2];
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
                 const int j = L + 64 * m + h * kHalf;
-                const uint32_t src = lane4 + shift4[m][h];
-                // With ACC stored as c = ~ACC, the step's  +-ACC[src] - ACC[j] + doffset  is
-                //   source not past X^N:  -c[src] + c[j] + doffset = (c[src] ^ ~0) + c[j] + doffset + 1
-                //   source past X^N:       c[src] + c[j] + doffset + 2
-                // i.e. (c[src] ^ flip) + c[j] + (doffset + 2 + flip) with flip = ~0 or 0: four instructions.
-                const uint32_t flip = (uint32_t)__builtin_amdgcn_sbfe((int32_t)src, 12u, 1u);
-                const uint32_t d = (rot[m][h] ^ flip) + my.acc[comp][j] + (doffset + 2u + flip);
+                const uint32_t d = (rot[m][h] ^ flip[m][h]) + my.acc[comp][j] + bias[m][h];
                 dig[h] = __builtin_amdgcn_sbfe((int32_t)d, dfield, (uint32_t)a.bgbit);    // signed field
             }
             x[m] = make_double2((double)dig[0], (double)dig[1]);
@@ -318,19 +321,20 @@ __device__ __forceinline__ void blind_rotate_body(const BlindRotateArgs &a) {
                                             : load_key(key_rsrc, voff, key_offset(i, part, r, o2));
 #pragma unroll
             for (int o2 = 0; o2 < 2; ++o2) {
-                // fused multiply-adds, two independent chains per output
+                // one chain of fused multiply-adds per real output (four independent chains per part)
                 const double2 d0 = x[q];
                 double yr = d0.x * k[0][o2].x, yi = d0.x * k[0][o2].y;
-                double zr = -d0.y * k[0][o2].y, zi = d0.y * k[0][o2].x;
+                yr = fma(-d0.y, k[0][o2].y, yr);
+                yi = fma(d0.y, k[0][o2].x, yi);
 #pragma unroll
                 for (int r = 1; r < 4; ++r) {
                     const double2 d = x[2 * r + q];
                     yr = fma(d.x, k[r][o2].x, yr);
                     yi = fma(d.x, k[r][o2].y, yi);
-                    zr = fma(-d.y, k[r][o2].y, zr);
-                    zi = fma(d.y, k[r][o2].x, zi);
+                    yr = fma(-d.y, k[r][o2].y, yr);
+                    yi = fma(d.y, k[r][o2].x, yi);
                 }
-                y[2 * (2 * (part & 1) + o2) + q] = make_double2(yr + zr, yi + zi);
+                y[2 * (2 * (part & 1) + o2) + q] = make_double2(yr, yi);
             }
         }
         const int next = i + 1 < a.n ? i + 1 : i;     // the last step requests its own row again
@@ -365,6 +369,7 @@ __device__ __forceinline__ void blind_rotate_body(const BlindRotateArgs &a) {
                 if (sel) r <<= 16;
                 if (m == 3 && h == 1) load_ahead(next, 4);
                 atomicAdd(&my.acc[comp][L + 64 * m + h * kHalf], r);
+                if (m == 0 && h == 0) atomicSub(&my.acc[comp][kN + L], r);      // the mirror holds -c - 2
             }
         }
         __syncthreads();
