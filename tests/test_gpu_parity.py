@@ -75,6 +75,30 @@ def test_every_gate_kind_ragged_batch(gpu, real_keys, op):
     assert list(T.tfhe_decrypt(sk, got)) == [TRUTH[op](int(x), int(y)) for x, y in zip(a, b)]
 
 
+def test_rotation_amounts_at_every_boundary(gpu, real_keys):
+    """Inputs built word by word (not encryptions) so that the rotation amounts a-bar of the 500
+    blind-rotation steps sit on the values where the rotated read changes shape: 0 (no rotation),
+    multiples of 64 (a lane-aligned wrap), one off them, N - 1, N, N + 1 (the sign change of
+    X^N = -1), 2N - 1, and the two ties of the rounding to 2N levels.  The oracle takes any words;
+    the bar is equal bytes.  (Sec. 3.2: the gate bootstrapping under every BNN gate.)"""
+    T, sk, ck = gpu
+    n = 500
+    special = [0, 1, 2, 31, 32, 63, 64, 65, 127, 128, 129, 511, 512, 513, 959, 960, 961, 1023, 1024, 1025,
+               1087, 1088, 1089, 1535, 1536, 1984, 2046, 2047]
+    rows = []
+    for v in special:                                   # the same amount in every step
+        rows.append(np.full(n + 1, v << 21, np.uint64))
+    for g in range(12):                                 # the amounts in turn, from a different start per gate
+        rows.append(np.array([special[(j * (g + 1) + g) % len(special)] << 21 for j in range(n + 1)], np.uint64))
+    for g, tie in enumerate([(1 << 20), (1 << 20) - 1, -(1 << 20), -(1 << 20) - 1]):   # on and beside a tie
+        rows.append(np.array([(special[(j + g) % len(special)] << 21) + tie for j in range(n + 1)], np.int64).astype(np.uint64))
+    cta = (np.stack(rows) & 0xFFFFFFFF).astype(np.uint32)
+    ctb = np.zeros_like(cta)
+    for op in ("OR", "NAND"):                           # multiplier +1 and -1 in front of the sum
+        got = run_batch(T, ck, op, cta, ctb)
+        assert np.array_equal(got, oracle_batch(real_keys, op, cta, ctb)), op
+
+
 def test_empty_and_in_place_batches(gpu, real_keys):
     import torch
     T, sk, ck = gpu
