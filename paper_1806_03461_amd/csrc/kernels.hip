@@ -141,7 +141,10 @@ __device__ __forceinline__ double2 load_key(__amdgpu_buffer_rsrc_t rsrc, uint32_
 // 4 x 16 clocks per wave, and a wave alone on its SIMD cannot issue anything else meanwhile, so
 // portions issued back to back stall all four waves (measured on 64 gates: all 32 loads in one
 // place 2.06 ms, two places 1.82 ms, four 1.71 ms, eight 1.62 ms; no key traffic at all 1.50 ms).
-// At full occupancy other workgroups cover the loads and holding registers for them does not pay.
+// At full occupancy other workgroups cover the loads and holding registers for them does not pay:
+// with two parts kept in flight (registers freed by moving the pass-2 twiddles to LDS) a launch of
+// 65,536 gates took 390-410 ms instead of 266-278.  The wait for a key row that no workgroup of the
+// XCD has touched yet is what keeps the workgroups of an XCD within the few rows its L2 holds.
 template <bool MARGIN, int AHEAD>
 __device__ __forceinline__ void blind_rotate_body(const BlindRotateArgs &a) {
     extern __shared__ __align__(16) unsigned char lds_raw[];
