@@ -48,6 +48,12 @@ KS_ALGORITHMIC_OPS = 1024 * 8 * 3 // 4 * 501
 KS_DENSE_OPS = 2 * 32768 * 512 * 4
 
 
+def progress(msg):
+    """A line on stderr when a part of the run has ended (stdout carries the one JSON line only)."""
+    sys.stderr.write("[bench] " + msg + "\n")
+    sys.stderr.flush()
+
+
 def plain_dense(x, W, T):
     """Popcount of agreeing (input, weight) pairs per unit; thresholded when T is given."""
     xs = 2 * x.astype(np.int64) - 1
@@ -103,6 +109,7 @@ def main():
     P = T.default_params()
     sk, ck = T.tfhe_keygen(P, workloads.KEY_SEED)
     T.tfhe_cloud_key_upload(ck)
+    progress("keys generated and uploaded")
     words = P.n + 1
     flags = {"folded": T.LOWER_DEFAULT, "mux": T.LOWER_MUX_COMPARATOR,
              "sort": T.LOWER_SORTING_NETWORK}[args.comparator]
@@ -206,8 +213,10 @@ def main():
                 h = buf
 
     # ---- warm-up, then exactly --steps timed steps between two synchronisations ----
-    for _ in range(args.warmup):
+    for k in range(args.warmup):
         step()
+        torch.cuda.synchronize()
+        progress(f"warm-up step {k + 1} of {args.warmup} done")
     torch.cuda.synchronize()
     T.tfhe_profile_enable(ck, True)
     T.tfhe_profile_read(ck, reset=True)
@@ -217,8 +226,13 @@ def main():
     for k in range(args.steps):
         step()
         marks[k + 1].record()       # on the stream the calls enqueue on: when this step's last kernel ends
+    for k in range(args.steps):     # the host only waits here; one line as each step's last kernel ends
+        marks[k + 1].synchronize()
+        if k + 1 < args.steps:
+            progress(f"timed step {k + 1} of {args.steps} done")
     torch.cuda.synchronize()
     t1 = time.perf_counter()
+    progress(f"timed step {args.steps} of {args.steps} done")
     prof = T.tfhe_profile_read(ck, reset=True)
     T.tfhe_profile_enable(ck, False)
     per_step_ms = [marks[k].elapsed_time(marks[k + 1]) for k in range(args.steps)]
@@ -321,9 +335,11 @@ def main():
             wires = np.zeros((3 * ng, words), np.uint32)
             wires[:ng], wires[ng:2 * ng] = ha[:ng], hb[:ng]
             what = f"first {ng} gates of the {args.workload} batch"
+        progress(f"CPU oracle: {what} on {threads} threads")
         t0 = time.perf_counter()
         keys.gate_batch(sample, wires, threads)
         dt = time.perf_counter() - t0
+        progress(f"CPU oracle: done in {dt:.1f} s")
         # one thread on the 16 gates of configuration 1
         c1 = workloads.cfg1()
         ca, cb = keys.encrypt(c1["a"], c1["enc_seed"]), keys.encrypt(c1["b"], c1["enc_seed"] + 1)

@@ -33,6 +33,19 @@ def toy_keys(orc):
     return orc.Keys(P, 4242)
 
 
+@pytest.fixture
+def say(request):
+    """Progress lines of long GPU tests, written past pytest's capture: whoever watches the run sees
+    each finished step of the work, not a silent process."""
+    capture = request.config.pluginmanager.getplugin("capturemanager")
+
+    def _say(msg):
+        with capture.global_and_fixture_disabled():
+            sys.stderr.write(msg + "\n")
+            sys.stderr.flush()
+    return _say
+
+
 def pytest_runtest_logstart(nodeid, location):
     """One unbuffered line per test: long GPU tests must not look like a hung run to whoever
     watches the output through a pipe."""
