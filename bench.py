@@ -223,13 +223,17 @@ def main():
     marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     t0 = time.perf_counter()
     marks[0].record()
+    done = 0
     for k in range(args.steps):
         step()
         marks[k + 1].record()       # on the stream the calls enqueue on: when this step's last kernel ends
-    for k in range(args.steps):     # the host only waits here; one line as each step's last kernel ends
-        marks[k + 1].synchronize()
-        if k + 1 < args.steps:
-            progress(f"timed step {k + 1} of {args.steps} done")
+        while done < k and marks[done + 1].query():      # non-blocking: steps whose last kernel has ended
+            done += 1
+            progress(f"timed step {done} of {args.steps} done")
+    while done + 1 < args.steps:    # the host only waits from here on; one line as each step ends
+        marks[done + 1].synchronize()
+        done += 1
+        progress(f"timed step {done} of {args.steps} done")
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     progress(f"timed step {args.steps} of {args.steps} done")
